@@ -1,0 +1,31 @@
+"""CPU oracle for bf16 flash attention (forward + backward).
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product path (the HIP library and its
+Python binding) may import this package; only the test-suite, the smoke check and
+the benchmark's CPU-baseline leg do.  It shares no code with the GPU path.
+
+Modules
+-------
+bf16        software bfloat16 rounding (round-to-nearest, ties-to-even) on numpy arrays
+exact       fp64 attention forward/backward written from the plain definitions
+            (Sec. 2.2 of the paper: O = softmax(alpha Q K^T) V, delta, dS, dQ/dK/dV)
+flash       the tiled algorithms (Alg. 1, Alg. 2, Alg. 3 of the paper) taken step by
+            step, with a pluggable working precision and explicit bf16 rounding points
+metrics     error measures used by the parity tests (max-abs, relative L2, mean signed)
+
+Pin status (see tests/test_oracle_*.py, all CPU-only):
+  bf16.round_to_bf16 .......... pinned (worked addition example of Sec. 3.3.2, exhaustive
+                                16-bit neighbourhood checks, torch's own conversion)
+  exact.forward / backward .... pinned (finite differences, brute-force loops, closed forms,
+                                identities of Sec. 3.2 / Eq. 2)
+  flash.forward (fp64 mode) ... pinned (equals exact.forward for any tile size and both
+                                variants: shift invariance, Sec. 4)
+  flash.backward (fp64 mode) .. pinned (equals exact.backward)
+  flash.* in bf16 mode ........ pinned only through tolerance against exact.* and through
+                                the structural facts of Sec. 3.3.2 / Sec. 4 (P-bar == 1 at a
+                                row maximum, max P-bar < 1 once the rule fires, sign of the
+                                bias).  Bit-exact agreement of the GPU kernels with the bf16
+                                emulation is NOT claimed: parity unpinned at bit level,
+                                because matrix-core summation order and the hardware exp2
+                                differ from numpy's.
+"""

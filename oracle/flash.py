@@ -1,0 +1,181 @@
+"""The paper's tiled algorithms, step by step, in a chosen working precision
+(test infrastructure only).
+
+forward()   Alg. 1 (flash-attention forward) and Alg. 3 (the stabilised forward: Alg. 1 plus
+            the three extra steps that pick the normaliser m when a tile row has a repeated
+            maximum, Sec. 4).
+backward()  Alg. 2 (flash-attention backward).
+
+A `Precision` fixes the arithmetic:
+  FP64  every step in binary64, no rounding points.  In this mode the functions must agree
+        with oracle.exact to rounding error for every tile size and both variants (online
+        softmax is exact; Alg. 3 only changes the softmax shift, Sec. 4).
+  BF16  the low-precision dataflow the paper analyses (Sec. 3.3.2): operands are bf16 values,
+        every product/sum is carried in binary32, and results are rounded to bf16 at stated
+        points.  The rounding points and the reasons for them:
+          (r1) P-bar is rounded to bf16 before it is used (it is a bf16 tensor in the paper's
+               low-precision flow: the inputs of the P-bar V product are results of earlier
+               bf16 operations, Sec. 3.3.2);
+          (r2) the row sum l is taken over the ROUNDED P-bar, in binary32, so numerator and
+               denominator use the same numbers (the paper uses one tensor P-bar for both);
+          (r3) the unnormalised output O-bar = P-bar V is accumulated in binary32 over ALL key
+               tiles and rounded to bf16 once, BEFORE the division by l (the paper's
+               "(.)_lp": dot product in FP32, final result rounded to BF16; its analysed
+               setting is tile = N, Sec. 3.2);
+          (r4) O = O-bar / l is rounded to bf16 again when stored;
+          (r5) m, l and L stay in binary32;
+          (r6) backward: delta = rowsum(dO o O) uses the bf16 O of (r4) (this is delta_lp,
+               Claim 1); P = exp(S - L) in binary32 is rounded to bf16 only as the operand of
+               P^T dO; dS = P o (dP - delta) uses the binary32 P and is rounded to bf16 as the
+               operand of dS K and dS^T Q; accumulators are binary32; alpha multiplies the
+               binary32 dQ, dK accumulators once at the end; dQ, dK, dV are stored as bf16.
+        Scores S stay in binary32 and alpha is applied to the binary32 Q K^T (never by
+        pre-scaling Q in bf16).
+
+Rows of the score matrix are independent in the forward pass, so the query block size B_r has
+no numerical effect there and all rows are processed together; B_c (the key tile) matters for
+Alg. 3 because its test looks at one tile row at a time.
+"""
+from dataclasses import dataclass
+from typing import Callable
+
+import numpy as np
+
+from .bf16 import round_to_bf16
+
+STANDARD = 0    # Alg. 1
+MITIGATED = 1   # Alg. 3
+
+
+@dataclass(frozen=True)
+class Precision:
+    name: str
+    dtype: type
+    rnd: Callable
+
+
+FP64 = Precision("fp64", np.float64, lambda x: x)
+BF16 = Precision("bf16", np.float32, round_to_bf16)
+
+
+def _tile_scores(Qw, Kj, alpha, causal, k0, prec):
+    """alpha Q K_j^T for key tile starting at column k0 (Alg. 1 step 6), masked entries -inf."""
+    S = (Qw @ Kj.T) * prec.dtype(alpha)
+    if causal:
+        r = np.arange(Qw.shape[0])[:, None]
+        c = (k0 + np.arange(Kj.shape[0]))[None, :]
+        S = np.where(c > r, prec.dtype(-np.inf), S)
+    return S.astype(prec.dtype)
+
+
+def forward(Q, K, V, alpha, causal, variant=STANDARD, beta=2.0, eps=1e-3, Bc=None, prec=BF16):
+    """One head, Alg. 1 (variant 0) or Alg. 3 (variant 1).
+
+    Returns a dict:
+      O      [N,d]  output (bf16-valued in BF16 mode)
+      L      [N]    logsumexp  m + log l            (Alg. 1 step 12)
+      Obar   [N,d]  unnormalised output after rounding point (r3)
+      Oacc   [N,d]  unnormalised output before (r3) (working precision)
+      ell,m  [N]    final running sum / normaliser
+      fired  [N]    number of key tiles in which the Alg. 3 rule changed m' for the row
+      ones   [N]    number of entries with (rounded) P-bar exactly 1, counted when produced
+    """
+    dt = prec.dtype
+    Qw = np.asarray(Q, dtype=dt); Kw = np.asarray(K, dtype=dt); Vw = np.asarray(V, dtype=dt)
+    N, d = Qw.shape
+    Nk = Kw.shape[0]
+    Bc = Nk if Bc is None else int(Bc)
+    m = np.full(N, -np.inf, dtype=dt)          # Alg. 1 step 4
+    ell = np.zeros(N, dtype=dt)
+    acc = np.zeros((N, d), dtype=dt)
+    fired = np.zeros(N, dtype=np.int64)
+    ones = np.zeros(N, dtype=np.int64)
+    with np.errstate(invalid="ignore", over="ignore", divide="ignore"):
+        for k0 in range(0, Nk, Bc):            # Alg. 1 step 5
+            Kj = Kw[k0:k0 + Bc]; Vj = Vw[k0:k0 + Bc]
+            S = _tile_scores(Qw, Kj, alpha, causal, k0, prec)            # step 6
+            r_m = np.max(S, axis=1)                                       # Alg. 3: tile row max
+            m_prime = r_m
+            if variant == MITIGATED:
+                # Alg. 3 extra steps (Sec. 4): count entries within eps of the tile row max;
+                # if more than one, move the normaliser away from the max.
+                r_s = np.sum((r_m[:, None] - S) <= dt(eps), axis=1)
+                repeated = r_s > 1
+                m_prime = np.where((r_m > 0) & repeated, dt(beta) * r_m, r_m)
+                m_prime = np.where((r_m < 0) & repeated, dt(0.0), m_prime)
+                fired += (m_prime != r_m).astype(np.int64)
+            m_new = np.maximum(m, m_prime.astype(dt))                     # step 7 (running max)
+            # rows with nothing visible yet have m_new = -inf: they contribute nothing
+            safe_m = np.where(np.isneginf(m_new), dt(0.0), m_new)
+            Pbar = np.exp(S - safe_m[:, None]).astype(dt)                 # step 7
+            Phat = prec.rnd(Pbar).astype(dt)                              # (r1)
+            corr = np.where(np.isneginf(m), dt(0.0), np.exp(m - safe_m)).astype(dt)
+            ell = (corr * ell + np.sum(Phat, axis=1, dtype=dt)).astype(dt)   # step 7, (r2)
+            acc = (corr[:, None] * acc + Phat @ Vj).astype(dt)            # step 8
+            ones += np.sum(Phat == dt(1.0), axis=1)
+            m = m_new
+        Obar = prec.rnd(acc).astype(dt)                                    # (r3)
+        O = prec.rnd(Obar / ell[:, None]).astype(dt)                       # step 10, (r4)
+        L = (m + np.log(ell)).astype(dt)                                   # step 11
+    return {"O": O, "L": L, "Obar": Obar, "Oacc": acc, "ell": ell, "m": m,
+            "fired": fired, "ones": ones}
+
+
+def backward(Q, K, V, O, dO, L, alpha, causal, Bc=None, Br=None, prec=BF16):
+    """One head, Alg. 2.  O and L are the forward pass's outputs (O bf16-valued in BF16 mode).
+
+    Returns dQ, dK, dV (bf16-valued in BF16 mode) and delta = rowsum(dO o O) in working precision.
+    """
+    dt = prec.dtype
+    Qw = np.asarray(Q, dtype=dt); Kw = np.asarray(K, dtype=dt); Vw = np.asarray(V, dtype=dt)
+    Ow = np.asarray(O, dtype=dt); dOw = np.asarray(dO, dtype=dt); Lw = np.asarray(L, dtype=dt)
+    N, d = Qw.shape
+    Bc = N if Bc is None else int(Bc)
+    Br = N if Br is None else int(Br)
+    delta = np.sum(dOw * Ow, axis=1, dtype=dt)                            # Alg. 2 step 4
+    dQ = np.zeros((N, d), dtype=dt)                                       # step 3
+    dK = np.zeros((N, d), dtype=dt)
+    dV = np.zeros((N, d), dtype=dt)
+    with np.errstate(invalid="ignore", over="ignore"):
+        for k0 in range(0, N, Bc):                                        # step 5
+            Kj = Kw[k0:k0 + Bc]; Vj = Vw[k0:k0 + Bc]
+            for q0 in range(0, N, Br):                                    # step 7
+                Qi = Qw[q0:q0 + Br]; dOi = dOw[q0:q0 + Br]
+                S = (Qi @ Kj.T) * dt(alpha)                               # step 8
+                if causal:
+                    r = (q0 + np.arange(Qi.shape[0]))[:, None]
+                    c = (k0 + np.arange(Kj.shape[0]))[None, :]
+                    S = np.where(c > r, dt(-np.inf), S)
+                P = np.exp(S.astype(dt) - Lw[q0:q0 + Br, None]).astype(dt)   # step 9
+                dV[k0:k0 + Bc] += prec.rnd(P).astype(dt).T @ dOi          # step 10
+                dP = (dOi @ Vj.T).astype(dt)                              # step 11
+                dS = (P * (dP - delta[q0:q0 + Br, None])).astype(dt)      # step 12
+                dSr = prec.rnd(dS).astype(dt)
+                dQ[q0:q0 + Br] += dSr @ Kj                                # step 13
+                dK[k0:k0 + Bc] += dSr.T @ Qi                              # step 14
+    dQ = prec.rnd(dQ * dt(alpha)).astype(dt)
+    dK = prec.rnd(dK * dt(alpha)).astype(dt)
+    dV = prec.rnd(dV).astype(dt)
+    return dQ, dK, dV, delta
+
+
+def forward_backward_bh(Q, K, V, dO, alpha, causal, variant=STANDARD, beta=2.0, eps=1e-3,
+                        Bc=None, prec=BF16, heads=None):
+    """[B,H,N,d] wrapper over forward() then backward(); see oracle.exact.forward_backward_bh."""
+    Q = np.asarray(Q); B, H, N, d = Q.shape
+    dt = prec.dtype
+    out = {k: np.full((B, H, N, d), np.nan, dtype=dt) for k in ("O", "Obar", "dQ", "dK", "dV")}
+    for k in ("L", "delta"):
+        out[k] = np.full((B, H, N), np.nan, dtype=dt)
+    out["fired"] = np.zeros((B, H, N), dtype=np.int64)
+    out["ones"] = np.zeros((B, H, N), dtype=np.int64)
+    todo = heads if heads is not None else [(b, h) for b in range(B) for h in range(H)]
+    for (b, h) in todo:
+        f = forward(Q[b, h], K[b, h], V[b, h], alpha, causal, variant, beta, eps, Bc, prec)
+        dQ, dK, dV, delta = backward(Q[b, h], K[b, h], V[b, h], f["O"], dO[b, h], f["L"],
+                                     alpha, causal, Bc, None, prec)
+        out["O"][b, h] = f["O"]; out["Obar"][b, h] = f["Obar"]; out["L"][b, h] = f["L"]
+        out["dQ"][b, h] = dQ; out["dK"][b, h] = dK; out["dV"][b, h] = dV
+        out["delta"][b, h] = delta
+        out["fired"][b, h] = f["fired"]; out["ones"][b, h] = f["ones"]
+    return out

@@ -1,0 +1,154 @@
+"""Seeded synthetic workloads for the attention kernels.
+
+This module only draws random numbers and arranges them; it holds none of the attention
+arithmetic and is imported neither by the HIP library's binding nor by the CPU oracle.
+Tests and the benchmark hand its outputs to both.
+
+The paper's own workload is GPT-2-small attention during OpenWebText pre-training
+(12 heads, head dimension 64, context 1024, causal; Sec. 3.1).  Those activations are not
+available, so every workload here is a stand-in with the same shapes and with the structure
+the paper identifies as relevant: peaky rows, low-rank Q/K, repeated row maxima, and (for the
+"skew" variant) value / upstream-gradient columns of one sign (Sec. 3.3.2, Claim 3).
+
+Every tensor is drawn in binary32, scaled, and rounded ONCE to bfloat16 by torch's own
+conversion; all implementations then see exactly those bf16 values.  Each (tensor, batch, head)
+slice has its own Philox stream, so one head of a large workload can be regenerated alone.
+"""
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    B: int
+    H: int
+    N: int
+    d: int
+    causal: bool
+    seed: int
+    qk_scale: float = 1.0       # multiplies the N(0,1) draws of Q and K
+    kind: str = "iid"           # "iid" | "tied" | "pairs"
+    dup_fraction: float = 0.25  # tied: share of K rows overwritten by a copy of another row
+    dup_scope: str = "block"    # tied: copy source within the same aligned 64-row block, or "any"
+    q_noise: float = 0.1        # tied: std of the noise added to the low-rank Q
+    q_coef: float = 0.5         # tied: std of Q's rank-2 coefficients (keeps |alpha q.k| below ~70, so
+                                # that (beta-1) * rowmax stays inside binary32's exponent range: the
+                                # stabilised forward underflows otherwise, Sec. 4)
+    skew: bool = False          # V <- -|skew_mu + skew_sigma z|, dO <- -|z|  (one-signed columns)
+    skew_mu: float = 0.0
+    skew_sigma: float = 1.0
+    pair_gain: float = 3.0      # pairs: query = gain * (its target key) + noise
+
+    @property
+    def alpha(self):
+        return 1.0 / float(np.sqrt(self.d))
+
+    def flops_fwd_bwd(self):
+        """Useful matrix-core FLOPs of one forward + backward: 2 + 5 contractions of
+        2 N^2 d each per head, halved under the causal mask."""
+        f = 14.0 * self.B * self.H * float(self.N) ** 2 * self.d
+        return f / 2 if self.causal else f
+
+
+WORKLOADS = {
+    # smallest case: both variants against the fp64 oracle + finite differences
+    "tiny": Workload("tiny", 1, 1, 128, 64, False, 1001),
+    # GPT-2-small attention shape, peaky softmax
+    "gpt2s": Workload("gpt2s", 8, 12, 1024, 64, True, 1002, qk_scale=1.5),
+    # repeated-row-maxima stress (rank-2 Q/K, duplicated K rows)
+    "tied": Workload("tied", 4, 12, 1024, 64, True, 1003, kind="tied"),
+    "tied_any": Workload("tied_any", 4, 12, 1024, 64, True, 1003, kind="tied", dup_scope="any"),
+    # same, with one-signed V and dO: the setting in which the rounding bias has a sign
+    "tied_skew": Workload("tied_skew", 4, 12, 1024, 64, True, 1003, kind="tied", skew=True),
+    "tied_any_skew": Workload("tied_any_skew", 4, 12, 1024, 64, True, 1003, kind="tied",
+                              dup_scope="any", skew=True),
+    # peaky rows whose maximum is attained by exactly two bit-identical keys (retrieval-like
+    # heads): every key vector occurs twice in a row (positions 2i, 2i+1), each query is a scaled
+    # copy of one visible key plus noise, so its two matching scores tie and every other
+    # probability is ~1e-6.  With the one-signed V this is the setting of Sec. 3.3.2 / Claim 3
+    # (V values around -2.3 as in the paper's worked addition).
+    "pairs": Workload("pairs", 4, 12, 1024, 64, True, 1006, kind="pairs"),
+    "pairs_skew": Workload("pairs_skew", 4, 12, 1024, 64, True, 1006, kind="pairs", skew=True,
+                           skew_mu=2.3, skew_sigma=0.3),
+    # mid-scale training shape (the headline throughput case)
+    "mid": Workload("mid", 4, 32, 4096, 128, True, 1004),
+    # long context, sharp attention
+    "long": Workload("long", 1, 16, 16384, 128, True, 1005, qk_scale=2.0),
+}
+
+_TENSOR_ID = {"Q": 0, "K": 1, "V": 2, "dO": 3, "aux": 4}
+
+
+def _rng(w, tensor, b, h):
+    return np.random.Generator(np.random.Philox(key=[w.seed, (_TENSOR_ID[tensor] << 40) | (b * w.H + h)]))
+
+
+def _to_bf16(x32):
+    return torch.from_numpy(np.ascontiguousarray(x32, dtype=np.float32)).to(torch.bfloat16)
+
+
+def head(w, b, h):
+    """The four bf16 tensors [N,d] of one (batch, head) slice of workload w."""
+    N, d = w.N, w.d
+    if w.kind == "iid":
+        Q = _to_bf16(w.qk_scale * _rng(w, "Q", b, h).standard_normal((N, d), dtype=np.float32))
+        K = _to_bf16(w.qk_scale * _rng(w, "K", b, h).standard_normal((N, d), dtype=np.float32))
+    elif w.kind == "tied":
+        aux = _rng(w, "aux", b, h)
+        M = aux.standard_normal((2, d), dtype=np.float32)           # shared rank-2 basis
+        A_k = _rng(w, "K", b, h).standard_normal((N, 2), dtype=np.float32)
+        gq = _rng(w, "Q", b, h)
+        A_q = np.float32(w.q_coef) * gq.standard_normal((N, 2), dtype=np.float32)
+        noise = w.q_noise * gq.standard_normal((N, d), dtype=np.float32)
+        K = _to_bf16(A_k @ M)
+        Q = _to_bf16(A_q @ M + noise)
+        # overwrite a share of K rows by bit-identical copies of other rows
+        n_dup = int(round(w.dup_fraction * N))
+        dst = aux.permutation(N)[:n_dup]
+        if w.dup_scope == "block":
+            blk = (dst // 64) * 64
+            src = blk + aux.integers(0, 64, size=n_dup)
+            src = np.minimum(src, N - 1)
+        else:
+            src = aux.integers(0, N, size=n_dup)
+        Kc = K.clone()
+        K[torch.from_numpy(dst)] = Kc[torch.from_numpy(src)]
+    elif w.kind == "pairs":
+        gk = _rng(w, "K", b, h)
+        base = gk.standard_normal((N // 2, d), dtype=np.float32)
+        K = _to_bf16(np.repeat(base, 2, axis=0))
+        gq = _rng(w, "Q", b, h)
+        r = np.arange(N)
+        tgt = np.minimum((gq.random(N) * (r // 2 + 1)).astype(np.int64), r // 2)   # a visible pair
+        noise = w.q_noise * gq.standard_normal((N, d), dtype=np.float32)
+        Q = _to_bf16(np.float32(w.pair_gain) * base[tgt] + noise)
+    else:
+        raise ValueError(w.kind)
+    V32 = _rng(w, "V", b, h).standard_normal((N, d), dtype=np.float32)
+    dO32 = _rng(w, "dO", b, h).standard_normal((N, d), dtype=np.float32)
+    if w.skew:
+        V32 = -np.abs(np.float32(w.skew_mu) + np.float32(w.skew_sigma) * V32); dO32 = -np.abs(dO32)
+    return {"Q": Q, "K": K, "V": _to_bf16(V32), "dO": _to_bf16(dO32)}
+
+
+def make(w, device=None):
+    """All heads of workload w as contiguous bf16 tensors [B,H,N,d] (on `device` if given)."""
+    if isinstance(w, str):
+        w = WORKLOADS[w]
+    out = {k: torch.empty((w.B, w.H, w.N, w.d), dtype=torch.bfloat16) for k in ("Q", "K", "V", "dO")}
+    for b in range(w.B):
+        for h in range(w.H):
+            t = head(w, b, h)
+            for k in out:
+                out[k][b, h] = t[k]
+    if device is not None:
+        out = {k: v.to(device) for k, v in out.items()}
+    return out
+
+
+def head_f64(w, b, h):
+    """One head's tensors as float64 numpy arrays (exact copies of the bf16 values)."""
+    return {k: v.to(torch.float64).numpy() for k, v in head(w, b, h).items()}

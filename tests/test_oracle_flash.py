@@ -1,0 +1,207 @@
+"""Pins for oracle.flash (CPU only).
+
+In fp64 mode the tiled algorithms (Alg. 1, 2, 3) must reproduce oracle.exact for every tile
+size and both variants (online softmax is exact; Alg. 3 only changes the softmax shift, Sec. 4).
+In bf16 mode the structural facts of Sec. 3.3.2 and Sec. 4 are checked: unit probabilities at a
+row maximum, none once the rule fires, the sign of the resulting bias and its removal.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from oracle import exact, flash, metrics
+from oracle.bf16 import is_bf16_valued
+from paper_2510_04212_amd import synth
+
+
+def _rand(seed, N, d, scale=1.0):
+    rng = np.random.default_rng(seed)
+    return [scale * rng.standard_normal((N, d)) for _ in range(4)]
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("variant", [flash.STANDARD, flash.MITIGATED])
+@pytest.mark.parametrize("Bc", [1, 7, 16, 50])
+def test_fp64_tiled_forward_equals_definition(causal, variant, Bc):
+    Q, K, V, _ = _rand(Bc, 50, 6, 1.5)
+    K[13] = K[4]; K[14] = K[4]; K[40] = K[39]       # repeated maxima so that Alg. 3 fires
+    O, L = exact.forward(Q, K, V, 0.4, causal)
+    f = flash.forward(Q, K, V, 0.4, causal, variant, beta=2.0, eps=1e-3, Bc=Bc, prec=flash.FP64)
+    assert np.max(np.abs(f["O"] - O)) < 1e-13
+    assert np.max(np.abs(f["L"] - L)) < 1e-13
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("Bc,Br", [(50, 50), (16, 8), (7, 50), (1, 1)])
+def test_fp64_tiled_backward_equals_definition(causal, Bc, Br):
+    Q, K, V, dO = _rand(77, 50, 6)
+    O, L = exact.forward(Q, K, V, 0.4, causal)
+    dQ, dK, dV, delta = exact.backward(Q, K, V, dO, 0.4, causal)
+    g = flash.backward(Q, K, V, O, dO, L, 0.4, causal, Bc=Bc, Br=Br, prec=flash.FP64)
+    for a, b in zip(g, (dQ, dK, dV, delta)):
+        assert np.max(np.abs(a - b)) < 1e-13
+
+
+def test_alg3_rule_values():
+    """Sec. 4: with a repeated positive tile maximum m = beta r_m, with a repeated negative one
+    m = 0, otherwise m = r_m (checked untiled, where m is exactly the rule's output)."""
+    d = 4
+    K = np.zeros((6, d)); K[:, 0] = [1.0, 3.0, 3.0, 0.5, -1.0, 2.0]
+    V = np.arange(24, dtype=np.float64).reshape(6, d)
+    Q = np.zeros((4, d)); Q[:, 0] = [1.0, -1.0, 0.0, 2.0]
+    # row 0: scores = K[:,0]      -> max 3 twice, positive  -> m = beta*3
+    # row 1: scores = -K[:,0]     -> max 1 once             -> m = 1
+    # row 2: all zero             -> max 0 repeated, neither branch -> m = 0 (= r_m)
+    # row 3: 2*K                  -> max 6 twice            -> m = beta*6
+    f = flash.forward(Q, K, V, 1.0, False, flash.MITIGATED, beta=2.5, eps=1e-3, prec=flash.FP64)
+    assert np.allclose(f["m"], [7.5, 1.0, 0.0, 15.0])
+    assert list(f["fired"]) == [1, 0, 0, 1]
+    Q2 = -Q.copy(); K2 = K.copy(); K2[:, 0] = [1.0, 3.0, 3.0, 5.0, 4.0, 2.0]
+    # row 0 of Q2: scores = -K2 -> max -1 once -> m=-1 ; make a repeated negative max:
+    K2[0, 0] = 2.0                  # scores row 0: -2,-3,-3,-5,-4,-2 -> max -2 twice -> m = 0
+    f = flash.forward(Q2[:1], K2, V, 1.0, False, flash.MITIGATED, prec=flash.FP64)
+    assert f["m"][0] == 0.0 and f["fired"][0] == 1
+    # eps: entries within eps of the max count as repeats, entries further away do not
+    K3 = K.copy(); K3[:, 0] = [1.0, 3.0, 3.0 - 5e-4, 0.0, 0.0, 0.0]
+    f = flash.forward(Q[:1], K3, V, 1.0, False, flash.MITIGATED, eps=1e-3, prec=flash.FP64)
+    assert f["fired"][0] == 1
+    f = flash.forward(Q[:1], K3, V, 1.0, False, flash.MITIGATED, eps=1e-4, prec=flash.FP64)
+    assert f["fired"][0] == 0
+
+
+def test_alg3_detection_is_per_key_tile():
+    """Alg. 3 inspects one tile row at a time: equal maxima that fall into different key tiles
+    are not detected, while the untiled run (tile = N, the paper's analysed setting) sees them."""
+    d = 2
+    K = np.zeros((8, d)); K[:, 0] = [4.0, 0, 0, 0, 0, 4.0, 0, 0]
+    V = np.ones((8, d)); Q = np.zeros((1, d)); Q[0, 0] = 1.0
+    f = flash.forward(Q, K, V, 1.0, False, flash.MITIGATED, Bc=4, prec=flash.FP64)
+    assert f["fired"][0] == 0
+    f = flash.forward(Q, K, V, 1.0, False, flash.MITIGATED, Bc=8, prec=flash.FP64)
+    assert f["fired"][0] == 1
+
+
+def _bf16_head(name, b=0, h=0):
+    w = synth.WORKLOADS[name]
+    return w, synth.head_f64(w, b, h)
+
+
+def test_bf16_mode_outputs_are_bf16_and_close_to_fp64():
+    w, x = _bf16_head("tiny")
+    for v in x.values():
+        assert is_bf16_valued(v)
+    O, L, dQ, dK, dV, delta = exact.forward_backward(x["Q"], x["K"], x["V"], x["dO"], w.alpha, w.causal)
+    for variant in (flash.STANDARD, flash.MITIGATED):
+        f = flash.forward(x["Q"], x["K"], x["V"], w.alpha, w.causal, variant, Bc=64)
+        g = flash.backward(x["Q"], x["K"], x["V"], f["O"], x["dO"], f["L"], w.alpha, w.causal, Bc=64)
+        assert is_bf16_valued(f["O"]) and is_bf16_valued(f["Obar"]) and all(is_bf16_valued(t) for t in g[:3])
+        # l sums the bf16-ROUNDED P-bar (rounding point r2): each term carries a relative error
+        # of up to 2^-9, so L = m + log l differs from the fp64 logsumexp by up to ~2e-3
+        assert np.max(np.abs(f["L"] - L)) < 2e-3
+        for a, r in ((f["O"], O), (g[0], dQ), (g[1], dK), (g[2], dV)):
+            assert metrics.max_abs(a, r) < 2e-2
+            assert metrics.rel_l2(a, r) < 1e-2
+
+
+def test_bf16_tiling_changes_results_only_at_rounding_level():
+    w, x = _bf16_head("gpt2s")
+    a = flash.forward(x["Q"], x["K"], x["V"], w.alpha, True, flash.STANDARD, Bc=64)
+    b = flash.forward(x["Q"], x["K"], x["V"], w.alpha, True, flash.STANDARD, Bc=1024)
+    assert metrics.rel_l2(a["O"], b["O"]) < 4e-3
+    assert np.max(np.abs(a["L"] - b["L"])) < 4e-3
+
+
+def test_bf16_constant_V_is_reproduced():
+    w, x = _bf16_head("tiny")
+    V = np.tile(x["V"][:1], (w.N, 1))
+    f = flash.forward(x["Q"], x["K"], V, w.alpha, False, flash.STANDARD, Bc=32)
+    rel = np.abs(f["O"] - V) / np.abs(V)
+    assert np.max(rel) <= 2.0 ** -7           # two bf16 roundings of an exactly proportional sum
+
+
+def test_unit_probabilities_standard_vs_mitigated():
+    """Sec. 3.3.2: in the safe softmax the entry at the row maximum has P-bar = exp(0) = 1;
+    Sec. 4: once the rule fires, every P-bar of the row is below 1."""
+    w, x = _bf16_head("pairs_skew")
+    std = flash.forward(x["Q"], x["K"], x["V"], w.alpha, True, flash.STANDARD, Bc=w.N)
+    mit = flash.forward(x["Q"], x["K"], x["V"], w.alpha, True, flash.MITIGATED, Bc=w.N)
+    assert np.all(std["ones"] >= 1)
+    assert np.mean(std["ones"] >= 2) > 0.95           # both copies of the matching key
+    fired = mit["fired"] > 0
+    assert fired.mean() > 0.95
+    assert np.all(mit["ones"][fired] == 0)
+    # the normaliser on fired rows is beta * (row max) for a positive max
+    S = exact.scores(x["Q"], x["K"], w.alpha, True)
+    r_m = S.max(1)
+    pos = fired & (r_m > 0)
+    assert np.allclose(mit["m"][pos], 2.0 * r_m[pos], rtol=1e-5)
+
+
+def test_bias_sign_and_its_removal_on_one_signed_values():
+    """Claim 3 / Sec. 3.3.2: with several unit probabilities and negative V the rounded
+    unnormalised output is biased negative, which makes delta_lp - delta_hp positive when dO
+    shares the sign; Alg. 3 removes it (Sec. 4)."""
+    w = synth.WORKLOADS["pairs_skew"]
+    e = {0: [], 1: []}; ebar = {0: [], 1: []}; dd = {0: [], 1: []}
+    for h in range(3):
+        x = synth.head_f64(w, 0, h)
+        O, L = exact.forward(x["Q"], x["K"], x["V"], w.alpha, True)
+        delta_hp = np.sum(x["dO"] * O, axis=1)
+        for variant in (0, 1):
+            f = flash.forward(x["Q"], x["K"], x["V"], w.alpha, True, variant, Bc=64)
+            e[variant].append((f["O"] - O).ravel())
+            ebar[variant].append((f["Obar"].astype(np.float64) - f["Oacc"]).ravel())
+            dd[variant].append(np.sum(x["dO"] * f["O"], axis=1) - delta_hp)
+    m = {v: float(np.concatenate(e[v]).mean()) for v in e}
+    noise = float(np.concatenate(e[0]).std() / np.sqrt(np.concatenate(e[0]).size))
+    assert m[0] < -50 * noise                       # a bias, far outside sampling noise
+    assert abs(m[1]) < abs(m[0]) / 10               # mitigated: at least 10x closer to zero
+    mb = {v: float(np.concatenate(ebar[v]).mean()) for v in ebar}
+    assert mb[0] < 0 and abs(mb[1]) < abs(mb[0]) / 10
+    d = {v: float(np.concatenate(dd[v]).mean()) for v in dd}
+    assert d[0] > 0 and abs(d[1]) < abs(d[0]) / 10
+
+
+def test_symmetric_values_show_no_bias():
+    """Every operation of the dataflow is odd-symmetric, so with V symmetric about zero the
+    expected signed error is zero in both variants."""
+    w = synth.WORKLOADS["pairs"]
+    for variant in (0, 1):
+        errs = []
+        for h in range(3):
+            x = synth.head_f64(w, 0, h)
+            O, _ = exact.forward(x["Q"], x["K"], x["V"], w.alpha, True)
+            f = flash.forward(x["Q"], x["K"], x["V"], w.alpha, True, variant, Bc=64)
+            errs.append((f["O"] - O).ravel())
+        e = np.concatenate(errs)
+        assert abs(e.mean()) < 5 * e.std() / np.sqrt(e.size)
+        # exact antisymmetry under V -> -V
+        x = synth.head_f64(w, 0, 0)
+        a = flash.forward(x["Q"], x["K"], x["V"], w.alpha, True, variant, Bc=64)["O"]
+        b = flash.forward(x["Q"], x["K"], -x["V"], w.alpha, True, variant, Bc=64)["O"]
+        assert np.array_equal(a, -b)
+
+
+def test_degenerate_cases():
+    d = 4
+    V = np.arange(1, 13, dtype=np.float64).reshape(3, d)
+    # (i) repeated maximum exactly 0: neither branch applies, unit probabilities remain
+    Q = np.zeros((1, d)); K = np.zeros((3, d))
+    f = flash.forward(Q, K, V, 1.0, False, flash.MITIGATED)
+    assert f["fired"][0] == 0 and f["ones"][0] == 3 and f["m"][0] == 0
+    # (ii) causal rows that see nothing in a later key tile are left untouched by that tile
+    rng = np.random.default_rng(0)
+    Q, K, V, _ = [rng.standard_normal((40, d)) for _ in range(4)]
+    a = flash.forward(Q, K, V, 0.5, True, flash.MITIGATED, Bc=8, prec=flash.FP64)
+    O, L = exact.forward(Q, K, V, 0.5, True)
+    assert np.isfinite(a["O"]).all() and np.max(np.abs(a["O"] - O)) < 1e-13
+    # (iii) the rule moves the exponent to -(beta-1) r_m: for a repeated maximum with
+    # (beta-1) r_m beyond binary32's range every term underflows and O is 0/0 -- the
+    # underflow the paper warns about for large beta (Sec. 4).  Literal behaviour, documented.
+    Q = np.zeros((1, d)); Q[0, 0] = 1.0
+    K = np.zeros((3, d)); K[:, 0] = [120.0, 120.0, 1.0]
+    f = flash.forward(Q, K, V, 1.0, False, flash.MITIGATED, beta=2.0)
+    assert f["ell"][0] == 0 and np.isnan(f["O"]).all()
+    f = flash.forward(Q, K, V, 1.0, False, flash.STANDARD)
+    assert np.isfinite(f["O"]).all()
