@@ -1,0 +1,155 @@
+#!/usr/bin/env python3
+"""Benchmark of the attention hot path on ONE MI355X.
+
+A "step" is one forward + one backward pass (attn_fwd, attn_delta, attn_bwd_dkdv, attn_bwd_dq --
+the same kernels attn_bwd launches) over one batch of synthetic bf16 inputs that are already
+resident in HBM.  Prints ONE JSON line.
+
+  metric   attention fwd+bwd TFLOP/s (bf16, causal): useful matrix-core FLOPs = 7 B H N^2 d
+           (2 forward + 5 backward contractions of 2 N^2 d, halved by the causal mask) / step time
+  roofline the longest-running kernel's algorithmic FLOPs / its mean duration (HIP events on the
+           launch stream, inside the timed steps) against the MI355X dense bf16 peak
+  cpu_baseline  the fp64 CPU oracle timed on a bounded number of heads of the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 matrix-core peak
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a copy
+# kernel of known size); filled in from the summaries under profiles/.  None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="mid", help="mid | long | gpt2s | tied | pairs_skew | tiny")
+    ap.add_argument("--variant", default="mitigated", choices=["standard", "mitigated"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (each GPU box has one); "
+              "--gpus must be 1. How the path would shard over GPUs is described in DESIGN.md.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2510_04212_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    w = synth.WORKLOADS[args.workload]
+    variant = binding.MITIGATED if args.variant == "mitigated" else binding.STANDARD
+    x = synth.make(w, dev)
+    B, H, N, d = w.B, w.H, w.N, w.d
+    O = torch.empty_like(x["Q"]); dQ = torch.empty_like(O); dK = torch.empty_like(O); dV = torch.empty_like(O)
+    L = torch.empty((B, H, N), dtype=torch.float32, device=dev)
+    delta = torch.empty((B, H, N), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(var, ev=None):
+        if ev: ev[0].record(stream)
+        binding.attn_fwd(x["Q"], x["K"], x["V"], w.causal, w.alpha, var, O=O, LSE=L, stream=stream)
+        if ev: ev[1].record(stream)
+        binding.attn_delta(O, x["dO"], delta, stream=stream)
+        if ev: ev[2].record(stream)
+        binding.attn_bwd_dkdv(x["Q"], x["K"], x["V"], x["dO"], L, delta, w.causal, w.alpha, dK=dK, dV=dV, stream=stream)
+        if ev: ev[3].record(stream)
+        binding.attn_bwd_dq(x["Q"], x["K"], x["V"], x["dO"], L, delta, w.causal, w.alpha, dQ=dQ, stream=stream)
+        if ev: ev[4].record(stream)
+
+    def timed(var, steps, warmup):
+        for _ in range(warmup):
+            step(var)
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(var, evs[i])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        names = ["fwd", "delta", "bwd_dkdv", "bwd_dq"]
+        per = {n: float(np.mean([evs[i][k].elapsed_time(evs[i][k + 1]) for i in range(steps)]))
+               for k, n in enumerate(names)}
+        return (t1 - t0) * 1e3 / steps, per
+
+    ms, per = timed(variant, args.steps, args.warmup)
+    other = binding.STANDARD if variant == binding.MITIGATED else binding.MITIGATED
+    ms_other, per_other = timed(other, max(3, args.steps // 2), 2)
+
+    flops = w.flops_fwd_bwd()
+    unit_c = flops / 7.0                     # FLOPs of one contraction over the whole batch
+    tflops = flops / (ms * 1e-3) / 1e12
+    # algorithmic FLOPs per launch: forward 2 contractions; dK/dV kernel 4 (S, dP, dV, dK);
+    # dQ kernel 1 (dQ; its recomputed S and dP are not counted)
+    alg = {"fwd": 2 * unit_c, "bwd_dkdv": 4 * unit_c, "bwd_dq": 1 * unit_c}
+    dom = max(alg, key=lambda k: per[k])
+    achieved = alg[dom] / (per[dom] * 1e-3) / 1e12
+    rows = B * H * N
+    delta_bytes = rows * (4 * d + 4)
+    out = {
+        "metric": "attention fwd+bwd TFLOP/s (bf16, causal)" if w.causal else "attention fwd+bwd TFLOP/s (bf16, non-causal)",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={B} H={H} N={N} d={d} causal={w.causal} softmax_scale=1/sqrt(d)",
+                   "variant": args.variant, "fwd_key_tile": binding.fwd_key_tile(d)},
+        "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
+        "kernel_ms": {k: round(v, 4) for k, v in per.items()},
+        "kernel_tflops": {k: round(alg[k] / (per[k] * 1e-3) / 1e12, 1) for k in alg},
+        "delta_pass": {"GB/s": round(delta_bytes / (per["delta"] * 1e-3) / 1e9, 1),
+                       "frac_of_hbm_peak": round(delta_bytes / (per["delta"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                       "bytes": delta_bytes},
+        "other_variant": {"variant": "standard" if other == binding.STANDARD else "mitigated",
+                          "ms_per_step": round(ms_other, 4),
+                          "value": round(flops / (ms_other * 1e-3) / 1e12, 2),
+                          "fwd_ms": round(per_other["fwd"], 4)},
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom))},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import exact
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count() or 1
+        heads_done = 0
+        t_cpu = 0.0
+        order = [(b, h) for b in range(B) for h in range(H)]
+        xs0 = synth.head_f64(w, 0, 0)
+        exact.forward_backward(xs0["Q"][:256], xs0["K"][:256], xs0["V"][:256], xs0["dO"][:256], w.alpha, w.causal)  # warm-up
+        while t_cpu < args.cpu_seconds and heads_done < len(order):
+            b, h = order[heads_done]
+            xs = synth.head_f64(w, b, h)
+            t0 = time.perf_counter()
+            exact.forward_backward(xs["Q"], xs["K"], xs["V"], xs["dO"], w.alpha, w.causal,
+                                   row_block=2048 if N > 2048 else None)
+            t_cpu += time.perf_counter() - t0
+            heads_done += 1
+        cpu_tflops = (flops / (B * H)) * heads_done / t_cpu / 1e12
+        out["cpu_baseline"] = {"value": round(cpu_tflops, 5), "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+                               "sample": f"fp64 numpy oracle (oracle.exact.forward_backward) on the first {heads_done} of "
+                                         f"{B * H} heads of the same workload, {t_cpu:.1f} s; FLOPs counted by the same "
+                                         f"causal-useful convention (the oracle itself forms the full N x N matrices)"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

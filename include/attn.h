@@ -1,0 +1,138 @@
+/*
+ * attn.h -- C ABI of the MI355X (gfx950) bf16 flash-attention library.
+ *
+ * What is computed (paper = "Why Low-Precision Transformer Training Fails: An Analysis on
+ * Flash Attention", arXiv 2510.04212):
+ *   forward   O = softmax(alpha Q K^T) V  and  L = rowwise logsumexp(alpha Q K^T)
+ *             by the tiled online-softmax algorithm (Alg. 1), or by its stabilised form
+ *             (Alg. 3, Sec. 4) which moves the softmax normaliser away from a repeated
+ *             row maximum so that no unnormalised probability is exactly 1;
+ *   backward  delta = rowsum(dO o O), P = exp(S - L), dV = P^T dO, dP = dO V^T,
+ *             dS = P o (dP - delta), dQ = alpha dS K, dK = alpha dS^T Q   (Alg. 2, Eq. 2).
+ *
+ * Conventions shared by every entry point
+ *   - Every pointer is a DEVICE pointer owned by the caller.  The library never allocates,
+ *     frees, copies to the host or synchronises; all work is enqueued on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream) and the call returns at once.
+ *   - Layout: contiguous [B][H][N][d], d fastest.  Q, K, V, O, dO, dQ, dK, dV are bfloat16;
+ *     LSE and delta are float32 [B][H][N].  Pointers must be 16-byte aligned.  Outputs must not
+ *     alias inputs.
+ *   - Self-attention: N queries and N keys.  causal != 0: query r attends to keys c <= r.
+ *   - Supported shapes: d in {64, 128}; N a positive multiple of 128; B*H*N*d < 2^40.
+ *     B == 0 or H == 0 is a no-op that returns ATTN_OK.  Anything else: ATTN_ERR_UNSUPPORTED.
+ *   - Return value: an attn_status.  No exceptions, aborts or global mutable state.
+ *   - Arithmetic: bf16 matrix-core products with float32 accumulation; scores, softmax
+ *     statistics and LSE in float32; the rounding points follow Sec. 3.3.2 of the paper:
+ *     the unnormalised probabilities P-bar are rounded to bf16 before use (and their rounded
+ *     values are what the row sum l adds up), the unnormalised output P-bar V is accumulated
+ *     in float32 over all key tiles, rounded to bf16 ONCE, then divided by l and rounded to
+ *     bf16 again.
+ */
+#ifndef PAPER_2510_04212_ATTN_H
+#define PAPER_2510_04212_ATTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ATTN_OK = 0,
+  ATTN_ERR_NULL = 1,         /* a required pointer is NULL */
+  ATTN_ERR_BAD_ARG = 2,      /* negative size, misaligned pointer, bad variant/beta/eps/scale */
+  ATTN_ERR_UNSUPPORTED = 3,  /* shape outside the supported set (see above) */
+  ATTN_ERR_WORKSPACE = 4,    /* workspace smaller than attn_bwd_workspace_bytes() */
+  ATTN_ERR_LAUNCH = 5        /* the HIP runtime refused a launch (hipGetLastError) */
+} attn_status;
+
+enum {
+  ATTN_VARIANT_STANDARD = 0,  /* Alg. 1: safe softmax, normaliser = running row maximum */
+  ATTN_VARIANT_MITIGATED = 1  /* Alg. 3: normaliser beta*r_m (r_m > 0) or 0 (r_m < 0) whenever a
+                                 key tile's row maximum r_m is attained (within eps) more than once */
+};
+
+/* Default parameters of the stabilised forward (Sec. 4: beta in [2,8], beta = 2 in the paper's
+ * training runs; eps "e.g. 1e-3"). */
+#define ATTN_DEFAULT_BETA 2.0f
+#define ATTN_DEFAULT_EPS 1e-3f
+
+/* Key-tile size B_c used by the forward kernel for head dimension d (0 if d is unsupported).
+ * Alg. 3 looks for a repeated maximum inside one key tile of one row, so its result depends on
+ * B_c; tiles start at multiples of B_c. */
+int attn_fwd_key_tile(int d);
+
+/*
+ * Forward pass (Alg. 1 / Alg. 3).
+ *   in : Q, K, V   bf16 [B,H,N,d]
+ *   out: O         bf16 [B,H,N,d];  LSE float32 [B,H,N] = m + log(l) in natural-log units of
+ *                  the alpha-scaled scores
+ *   softmax_scale  alpha > 0, multiplies the float32 Q K^T (Q is never pre-scaled in bf16)
+ *   variant        ATTN_VARIANT_*; attn_fwd uses ATTN_DEFAULT_BETA / ATTN_DEFAULT_EPS
+ * attn_fwd_ex additionally takes beta > 1 and eps >= 0 (both ignored by the standard variant).
+ * eps and the sign tests of Alg. 3 apply to the alpha-scaled scores.
+ * Note (Sec. 4, "larger values risk underflow"): when a repeated maximum satisfies
+ * (beta-1)*r_m > ~87, every exp underflows, l = 0 and that row of O is NaN; this is the
+ * algorithm's own limit and is not masked.
+ */
+int attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+             int B, int H, int N, int d, int causal, float softmax_scale, int variant,
+             void* stream);
+int attn_fwd_ex(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                int B, int H, int N, int d, int causal, float softmax_scale, int variant,
+                float beta, float eps, void* stream);
+
+/*
+ * delta = rowsum(dO o O)  (Alg. 2, step 4), float32 [B,H,N], from the bf16 O the forward pass
+ * stored (the low-precision delta of Claim 1).  Products and the row sum are float32.
+ * A pure streaming pass, bound by HBM bandwidth.
+ */
+int attn_delta(const void* O, const void* dO, float* delta, int B, int H, int N, int d,
+               void* stream);
+
+/*
+ * Backward pass (Alg. 2).
+ *   in : Q, K, V, O, dO  bf16 [B,H,N,d];  LSE float32 [B,H,N] from attn_fwd
+ *   out: dQ, dK, dV      bf16 [B,H,N,d]
+ *   workspace            device scratch of at least attn_bwd_workspace_bytes(B,H,N,d) bytes,
+ *                        256-byte aligned; holds delta [B,H,N] float32 (readable by the caller
+ *                        after the call: it starts at offset 0).  Contents on entry are ignored.
+ *   variant              accepted for symmetry and validated, but has no effect: Alg. 3 leaves the
+ *                        backward pass unchanged (Sec. 4).
+ * P = exp(S - L) is rounded to bf16 as the operand of P^T dO; dS = P o (dP - delta) uses the
+ * float32 P and is rounded to bf16 as the operand of dS K and dS^T Q; alpha multiplies the
+ * float32 dQ / dK accumulators once; results are rounded to bf16 when stored.
+ * Deterministic: no atomics, results are bit-identical from run to run.
+ */
+int attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+             const float* LSE, void* dQ, void* dK, void* dV,
+             void* workspace, size_t workspace_bytes,
+             int B, int H, int N, int d, int causal, float softmax_scale, int variant,
+             void* stream);
+size_t attn_bwd_workspace_bytes(int B, int H, int N, int d);
+
+/*
+ * The two main stages of attn_bwd, exposed separately so that a caller can time them
+ * (attn_bwd == attn_delta into the workspace, then attn_bwd_dkdv, then attn_bwd_dq).
+ * `delta` is float32 [B,H,N] as produced by attn_delta.  Same layouts, checks and error codes
+ * as attn_bwd.
+ *   attn_bwd_dkdv  Alg. 2 steps 8-12 and 10/14 for one key block per work-group:
+ *                  S = Q K^T, P = exp(S - L), dP = dO V^T, dS = P o (dP - delta),
+ *                  dV = P^T dO, dK = alpha dS^T Q.
+ *   attn_bwd_dq    Alg. 2 steps 8-13 for one query block per work-group (S and dP recomputed):
+ *                  dQ = alpha dS K.
+ */
+int attn_bwd_dkdv(const void* Q, const void* K, const void* V, const void* dO, const float* LSE,
+                  const float* delta, void* dK, void* dV,
+                  int B, int H, int N, int d, int causal, float softmax_scale, void* stream);
+int attn_bwd_dq(const void* Q, const void* K, const void* V, const void* dO, const float* LSE,
+                const float* delta, void* dQ,
+                int B, int H, int N, int d, int causal, float softmax_scale, void* stream);
+
+/* Human-readable name of an attn_status (static storage, never NULL). */
+const char* attn_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

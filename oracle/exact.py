@@ -74,14 +74,39 @@ def backward(Q, K, V, dO, alpha, causal, delta=None):
     return dQ, dK, dV, delta
 
 
-def forward_backward(Q, K, V, dO, alpha, causal):
-    """One head, everything at once: O, L, dQ, dK, dV, delta."""
-    O, L = forward(Q, K, V, alpha, causal)
-    dQ, dK, dV, delta = backward(Q, K, V, dO, alpha, causal)
+def forward_backward(Q, K, V, dO, alpha, causal, row_block=None):
+    """One head, everything at once: O, L, dQ, dK, dV, delta.
+
+    Query rows are independent of one another in S, P, O, L, delta, dP, dS and dQ, and dK, dV are
+    sums over query rows; `row_block` only bounds memory by visiting the rows in slabs
+    (row_block=None: one slab, i.e. the full N x N matrices).  The arithmetic per entry is the
+    same as in forward() / backward().
+    """
+    Q = np.asarray(Q, dtype=np.float64); K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64); dO = np.asarray(dO, dtype=np.float64)
+    N, d = Q.shape
+    rb = N if row_block is None else int(row_block)
+    O = np.empty((N, d)); L = np.empty(N); delta = np.empty(N)
+    dQ = np.empty((N, d)); dK = np.zeros((N, d)); dV = np.zeros((N, d))
+    for r0 in range(0, N, rb):
+        r1 = min(N, r0 + rb)
+        S = alpha * (Q[r0:r1] @ K.T)
+        if causal:
+            r = np.arange(r0, r1)[:, None]
+            c = np.arange(N)[None, :]
+            S = np.where(c > r, -np.inf, S)
+        P, L[r0:r1] = softmax_rows(S)
+        O[r0:r1] = P @ V
+        delta[r0:r1] = np.sum(dO[r0:r1] * O[r0:r1], axis=1)
+        dV += P.T @ dO[r0:r1]
+        dP = dO[r0:r1] @ V.T
+        dS = P * (dP - delta[r0:r1, None])
+        dQ[r0:r1] = alpha * (dS @ K)
+        dK += alpha * (dS.T @ Q[r0:r1])
     return O, L, dQ, dK, dV, delta
 
 
-def forward_backward_bh(Q, K, V, dO, alpha, causal, heads=None):
+def forward_backward_bh(Q, K, V, dO, alpha, causal, heads=None, row_block=None):
     """[B,H,N,d] wrapper.  `heads` = optional list of (b,h) pairs to compute (others skipped).
 
     Returns a dict of arrays shaped like the inputs ([B,H,N] for L and delta); entries of
@@ -93,7 +118,8 @@ def forward_backward_bh(Q, K, V, dO, alpha, causal, heads=None):
     out["delta"] = np.full((B, H, N), np.nan)
     todo = heads if heads is not None else [(b, h) for b in range(B) for h in range(H)]
     for (b, h) in todo:
-        O, L, dQ, dK, dV, delta = forward_backward(Q[b, h], K[b, h], V[b, h], dO[b, h], alpha, causal)
+        O, L, dQ, dK, dV, delta = forward_backward(Q[b, h], K[b, h], V[b, h], dO[b, h], alpha, causal,
+                                                     row_block)
         out["O"][b, h] = O; out["L"][b, h] = L
         out["dQ"][b, h] = dQ; out["dK"][b, h] = dK; out["dV"][b, h] = dV
         out["delta"][b, h] = delta

@@ -1,0 +1,168 @@
+"""Thin ctypes binding over the C ABI declared in include/attn.h.
+
+Argument marshalling only: every step of the attention forward/backward runs in the HIP
+kernels of libattn_gfx950.so.  torch is used for device memory and for the current stream.
+There is no fallback: if the library has not been built, importing this module raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libattn_gfx950.so")
+
+STANDARD = 0
+MITIGATED = 1
+DEFAULT_BETA = 2.0
+DEFAULT_EPS = 1e-3
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it first with `python -m paper_2510_04212_amd.build` "
+        "(there is no CPU or PyTorch fallback for the attention kernels)")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _i, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+_lib.attn_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _vp]
+_lib.attn_fwd.restype = _i
+_lib.attn_fwd_ex.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _f, _f, _vp]
+_lib.attn_fwd_ex.restype = _i
+_lib.attn_delta.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp]
+_lib.attn_delta.restype = _i
+_lib.attn_bwd.argtypes = [_vp] * 9 + [_vp, _sz, _i, _i, _i, _i, _i, _f, _i, _vp]
+_lib.attn_bwd.restype = _i
+_lib.attn_bwd_dkdv.argtypes = [_vp] * 8 + [_i, _i, _i, _i, _i, _f, _vp]
+_lib.attn_bwd_dkdv.restype = _i
+_lib.attn_bwd_dq.argtypes = [_vp] * 7 + [_i, _i, _i, _i, _i, _f, _vp]
+_lib.attn_bwd_dq.restype = _i
+_lib.attn_bwd_workspace_bytes.argtypes = [_i, _i, _i, _i]
+_lib.attn_bwd_workspace_bytes.restype = _sz
+_lib.attn_status_string.argtypes = [_i]
+_lib.attn_status_string.restype = ctypes.c_char_p
+_lib.attn_fwd_key_tile.argtypes = [_i]
+_lib.attn_fwd_key_tile.restype = _i
+
+EXPORTS = ["attn_fwd", "attn_fwd_ex", "attn_delta", "attn_bwd", "attn_bwd_dkdv", "attn_bwd_dq",
+           "attn_bwd_workspace_bytes",
+           "attn_status_string", "attn_fwd_key_tile"]
+
+
+class AttnError(RuntimeError):
+    def __init__(self, status):
+        self.status = int(status)
+        super().__init__(_lib.attn_status_string(int(status)).decode())
+
+
+def raw():
+    """The ctypes library object (for tests that call the C ABI with hand-made arguments)."""
+    return _lib
+
+
+def status_string(status):
+    return _lib.attn_status_string(int(status)).decode()
+
+
+def fwd_key_tile(d):
+    return int(_lib.attn_fwd_key_tile(int(d)))
+
+
+def bwd_workspace_bytes(B, H, N, d):
+    return int(_lib.attn_bwd_workspace_bytes(B, H, N, d))
+
+
+def _check(status):
+    if status != 0:
+        raise AttnError(status)
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _bhnd(t, name):
+    if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+        raise ValueError(f"{name} must be a contiguous CUDA bfloat16 tensor [B,H,N,d]")
+    return t.shape
+
+
+def attn_fwd(Q, K, V, causal, softmax_scale, variant=STANDARD, beta=None, eps=None,
+             O=None, LSE=None, stream=None):
+    """O, LSE = attention forward (attn_fwd / attn_fwd_ex of the C ABI)."""
+    B, H, N, d = _bhnd(Q, "Q")
+    for n, t in (("K", K), ("V", V)):
+        if _bhnd(t, n) != (B, H, N, d):
+            raise ValueError(f"{n} shape differs from Q")
+    if O is None:
+        O = torch.empty_like(Q)
+    if LSE is None:
+        LSE = torch.empty((B, H, N), dtype=torch.float32, device=Q.device)
+    if beta is None and eps is None:
+        st = _lib.attn_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), B, H, N, d, int(bool(causal)),
+                           float(softmax_scale), int(variant), _stream(stream))
+    else:
+        st = _lib.attn_fwd_ex(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), B, H, N, d, int(bool(causal)),
+                              float(softmax_scale), int(variant),
+                              float(DEFAULT_BETA if beta is None else beta),
+                              float(DEFAULT_EPS if eps is None else eps), _stream(stream))
+    _check(st)
+    return O, LSE
+
+
+def attn_delta(O, dO, delta=None, stream=None):
+    """delta = rowsum(dO o O), float32 [B,H,N]."""
+    B, H, N, d = _bhnd(O, "O")
+    if _bhnd(dO, "dO") != (B, H, N, d):
+        raise ValueError("dO shape differs from O")
+    if delta is None:
+        delta = torch.empty((B, H, N), dtype=torch.float32, device=O.device)
+    _check(_lib.attn_delta(_ptr(O), _ptr(dO), _ptr(delta), B, H, N, d, _stream(stream)))
+    return delta
+
+
+def attn_bwd(Q, K, V, O, dO, LSE, causal, softmax_scale, variant=STANDARD,
+             dQ=None, dK=None, dV=None, workspace=None, stream=None):
+    """dQ, dK, dV = attention backward.  `workspace` (uint8 CUDA tensor) is allocated when absent;
+    after the call its first B*H*N float32 hold delta."""
+    B, H, N, d = _bhnd(Q, "Q")
+    for n, t in (("K", K), ("V", V), ("O", O), ("dO", dO)):
+        if _bhnd(t, n) != (B, H, N, d):
+            raise ValueError(f"{n} shape differs from Q")
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(Q) if dK is None else dK
+    dV = torch.empty_like(Q) if dV is None else dV
+    need = bwd_workspace_bytes(B, H, N, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Q.device)
+    st = _lib.attn_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK),
+                       _ptr(dV), _ptr(workspace), workspace.numel(), B, H, N, d, int(bool(causal)),
+                       float(softmax_scale), int(variant), _stream(stream))
+    _check(st)
+    return dQ, dK, dV
+
+
+def attn_bwd_dkdv(Q, K, V, dO, LSE, delta, causal, softmax_scale, dK=None, dV=None, stream=None):
+    """Stage 2 of the backward pass alone: dK, dV (delta from attn_delta)."""
+    B, H, N, d = _bhnd(Q, "Q")
+    dK = torch.empty_like(Q) if dK is None else dK
+    dV = torch.empty_like(Q) if dV is None else dV
+    _check(_lib.attn_bwd_dkdv(_ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(LSE), _ptr(delta), _ptr(dK),
+                              _ptr(dV), B, H, N, d, int(bool(causal)), float(softmax_scale),
+                              _stream(stream)))
+    return dK, dV
+
+
+def attn_bwd_dq(Q, K, V, dO, LSE, delta, causal, softmax_scale, dQ=None, stream=None):
+    """Stage 3 of the backward pass alone: dQ (delta from attn_delta)."""
+    B, H, N, d = _bhnd(Q, "Q")
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    _check(_lib.attn_bwd_dq(_ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(LSE), _ptr(delta), _ptr(dQ),
+                            B, H, N, d, int(bool(causal)), float(softmax_scale), _stream(stream)))
+    return dQ

@@ -1,0 +1,173 @@
+// C ABI of the attention library (see include/attn.h): argument validation and dispatch only.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <cmath>
+#include "../../include/attn.h"
+
+hipError_t attn_fwd_dispatch(const void*, const void*, const void*, void*, float*, int, int, int,
+                             int, float, int, float, float, hipStream_t);
+hipError_t attn_delta_dispatch(const void*, const void*, float*, long, int, hipStream_t);
+hipError_t attn_bwd_dkdv_dispatch(const void*, const void*, const void*, const void*, const float*,
+                                  const float*, void*, void*, int, int, int, int, float,
+                                  hipStream_t);
+hipError_t attn_bwd_dq_dispatch(const void*, const void*, const void*, const void*, const float*,
+                                const float*, void*, int, int, int, int, float, hipStream_t);
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Shape check shared by all entry points.  Returns ATTN_OK with *empty = true for B*H == 0.
+int check_shape(int B, int H, int N, int d, bool* empty) {
+  *empty = false;
+  if (B < 0 || H < 0 || N < 0 || d < 0) return ATTN_ERR_BAD_ARG;
+  if (B == 0 || H == 0) { *empty = true; return ATTN_OK; }
+  if (d != 64 && d != 128) return ATTN_ERR_UNSUPPORTED;
+  if (N == 0 || (N % 128) != 0) return ATTN_ERR_UNSUPPORTED;
+  const double elems = (double)B * H * (double)N * d;
+  if (elems >= 1099511627776.0) return ATTN_ERR_UNSUPPORTED;      // 2^40
+  if ((double)B * H * (N / 128) >= 2147483648.0) return ATTN_ERR_UNSUPPORTED;
+  return ATTN_OK;
+}
+
+}  // namespace
+
+extern "C" const char* attn_status_string(int status) {
+  switch (status) {
+    case ATTN_OK: return "ATTN_OK";
+    case ATTN_ERR_NULL: return "ATTN_ERR_NULL: a required pointer is NULL";
+    case ATTN_ERR_BAD_ARG: return "ATTN_ERR_BAD_ARG: invalid argument value or misaligned pointer";
+    case ATTN_ERR_UNSUPPORTED: return "ATTN_ERR_UNSUPPORTED: d must be 64 or 128 and N a positive multiple of 128";
+    case ATTN_ERR_WORKSPACE: return "ATTN_ERR_WORKSPACE: workspace too small or misaligned";
+    case ATTN_ERR_LAUNCH: return "ATTN_ERR_LAUNCH: HIP launch failed";
+    default: return "unknown attn_status";
+  }
+}
+
+extern "C" int attn_fwd_ex(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                           int B, int H, int N, int d, int causal, float softmax_scale,
+                           int variant, float beta, float eps, void* stream) {
+  bool empty;
+  int st = check_shape(B, H, N, d, &empty);
+  if (st != ATTN_OK) return st;
+  if (variant != ATTN_VARIANT_STANDARD && variant != ATTN_VARIANT_MITIGATED) return ATTN_ERR_BAD_ARG;
+  if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale)) return ATTN_ERR_BAD_ARG;
+  if (variant == ATTN_VARIANT_MITIGATED) {
+    if (!(beta > 1.f) || !std::isfinite(beta)) return ATTN_ERR_BAD_ARG;
+    if (!(eps >= 0.f) || !std::isfinite(eps)) return ATTN_ERR_BAD_ARG;
+  }
+  if (empty) return ATTN_OK;
+  if (!Q || !K || !V || !O || !LSE) return ATTN_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE))
+    return ATTN_ERR_BAD_ARG;
+  if (O == Q || O == K || O == V) return ATTN_ERR_BAD_ARG;
+  hipError_t e = attn_fwd_dispatch(Q, K, V, O, LSE, B * H, N, d, causal, softmax_scale, variant,
+                                   beta, eps, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+extern "C" int attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
+                        int H, int N, int d, int causal, float softmax_scale, int variant,
+                        void* stream) {
+  return attn_fwd_ex(Q, K, V, O, LSE, B, H, N, d, causal, softmax_scale, variant,
+                     ATTN_DEFAULT_BETA, ATTN_DEFAULT_EPS, stream);
+}
+
+extern "C" int attn_delta(const void* O, const void* dO, float* delta, int B, int H, int N, int d,
+                          void* stream) {
+  bool empty;
+  int st = check_shape(B, H, N, d, &empty);
+  if (st != ATTN_OK) return st;
+  if (empty) return ATTN_OK;
+  if (!O || !dO || !delta) return ATTN_ERR_NULL;
+  if (!aligned16(O) || !aligned16(dO) || !aligned16(delta)) return ATTN_ERR_BAD_ARG;
+  hipError_t e = attn_delta_dispatch(O, dO, delta, (long)B * H * N, d,
+                                     static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+extern "C" size_t attn_bwd_workspace_bytes(int B, int H, int N, int d) {
+  bool empty;
+  if (check_shape(B, H, N, d, &empty) != ATTN_OK || empty) return 0;
+  size_t bytes = (size_t)B * H * N * sizeof(float);   // delta
+  return (bytes + 255) & ~(size_t)255;
+}
+
+// Checks shared by attn_bwd and its two stage entry points.
+static int check_bwd_common(int B, int H, int N, int d, float softmax_scale, bool* empty) {
+  int st = check_shape(B, H, N, d, empty);
+  if (st != ATTN_OK) return st;
+  if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale)) return ATTN_ERR_BAD_ARG;
+  return ATTN_OK;
+}
+
+extern "C" int attn_bwd_dkdv(const void* Q, const void* K, const void* V, const void* dO,
+                             const float* LSE, const float* delta, void* dK, void* dV, int B,
+                             int H, int N, int d, int causal, float softmax_scale, void* stream) {
+  bool empty;
+  int st = check_bwd_common(B, H, N, d, softmax_scale, &empty);
+  if (st != ATTN_OK) return st;
+  if (empty) return ATTN_OK;
+  if (!Q || !K || !V || !dO || !LSE || !delta || !dK || !dV) return ATTN_ERR_NULL;
+  const void* ptrs[] = {Q, K, V, dO, LSE, delta, dK, dV};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return ATTN_ERR_BAD_ARG;
+  const void* ins[] = {Q, K, V, dO};
+  for (const void* p : ins)
+    if (p == dK || p == dV) return ATTN_ERR_BAD_ARG;
+  if (dK == dV) return ATTN_ERR_BAD_ARG;
+  hipError_t e = attn_bwd_dkdv_dispatch(Q, K, V, dO, LSE, delta, dK, dV, B * H, N, d, causal,
+                                        softmax_scale, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+extern "C" int attn_bwd_dq(const void* Q, const void* K, const void* V, const void* dO,
+                           const float* LSE, const float* delta, void* dQ, int B, int H, int N,
+                           int d, int causal, float softmax_scale, void* stream) {
+  bool empty;
+  int st = check_bwd_common(B, H, N, d, softmax_scale, &empty);
+  if (st != ATTN_OK) return st;
+  if (empty) return ATTN_OK;
+  if (!Q || !K || !V || !dO || !LSE || !delta || !dQ) return ATTN_ERR_NULL;
+  const void* ptrs[] = {Q, K, V, dO, LSE, delta, dQ};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return ATTN_ERR_BAD_ARG;
+  const void* ins[] = {Q, K, V, dO};
+  for (const void* p : ins)
+    if (p == dQ) return ATTN_ERR_BAD_ARG;
+  hipError_t e = attn_bwd_dq_dispatch(Q, K, V, dO, LSE, delta, dQ, B * H, N, d, causal,
+                                      softmax_scale, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+extern "C" int attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                        const float* LSE, void* dQ, void* dK, void* dV, void* workspace,
+                        size_t workspace_bytes, int B, int H, int N, int d, int causal,
+                        float softmax_scale, int variant, void* stream) {
+  bool empty;
+  int st = check_shape(B, H, N, d, &empty);
+  if (st != ATTN_OK) return st;
+  if (variant != ATTN_VARIANT_STANDARD && variant != ATTN_VARIANT_MITIGATED) return ATTN_ERR_BAD_ARG;
+  if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale)) return ATTN_ERR_BAD_ARG;
+  if (empty) return ATTN_OK;
+  if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_NULL;
+  const void* ptrs[] = {Q, K, V, O, dO, LSE, dQ, dK, dV};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return ATTN_ERR_BAD_ARG;
+  const void* ins[] = {Q, K, V, O, dO};
+  for (const void* p : ins)
+    if (p == dQ || p == dK || p == dV) return ATTN_ERR_BAD_ARG;
+  if (dQ == dK || dQ == dV || dK == dV) return ATTN_ERR_BAD_ARG;
+  if (!workspace) return ATTN_ERR_NULL;
+  if (workspace_bytes < attn_bwd_workspace_bytes(B, H, N, d) ||
+      (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+    return ATTN_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float* delta = static_cast<float*>(workspace);
+  hipError_t e = attn_delta_dispatch(O, dO, delta, (long)B * H * N, d, s);
+  if (e != hipSuccess) return ATTN_ERR_LAUNCH;
+  e = attn_bwd_dkdv_dispatch(Q, K, V, dO, LSE, delta, dK, dV, B * H, N, d, causal, softmax_scale, s);
+  if (e != hipSuccess) return ATTN_ERR_LAUNCH;
+  e = attn_bwd_dq_dispatch(Q, K, V, dO, LSE, delta, dQ, B * H, N, d, causal, softmax_scale, s);
+  return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}

@@ -1,0 +1,338 @@
+// Flash-attention backward for gfx950 (Alg. 2 of arXiv 2510.04212), as two kernels so that no
+// gradient needs a cross-work-group reduction (no atomics, deterministic):
+//
+//   attn_bwd_dkdv_kernel  one work-group per (batch, head, 128-key block); K_j / V_j fragments
+//                         stay in registers, query tiles (Q_i, dO_i, L_i, delta_i; 64 rows) stream
+//                         through LDS.  Per tile:  S = Q_i K_j^T,  P = exp(S - L),  dP = dO_i V_j^T,
+//                         dS = P o (dP - delta),  dV_j^T += dO_i^T P,  dK_j^T += Q_i^T dS.
+//   attn_bwd_dq_kernel    one work-group per (batch, head, 128-query block); Q_i / dO_i fragments,
+//                         L_i and delta_i stay in registers, key tiles (K_j, V_j; 64 rows) stream
+//                         through LDS.  Per tile:  S^T = K_j Q_i^T,  dP^T = V_j dO_i^T,
+//                         dS^T = P^T o (dP^T - delta),  dQ_i^T += K_j^T dS^T.
+//
+// S and dP are recomputed in the second kernel (7 matrix products per tile pair instead of
+// Alg. 2's 5); in exchange every contraction finds its operands already in fragment layout:
+// the accumulator-layout P / dS tiles are fed back as B operands unchanged, and the operands
+// whose contraction index runs along tile rows come from transposing LDS reads.
+//
+// Rounding points: P (float32) -> bf16 as the operand of dO^T P; dS = P o (dP - delta) is formed
+// from the float32 P and rounded to bf16 as an operand; accumulators are float32; alpha
+// multiplies the float32 dQ / dK accumulators once; outputs are rounded to bf16 when stored.
+#include "common.hpp"
+
+namespace {
+
+constexpr int kKeysPerWG = 128;   // dK/dV kernel: keys per work-group (32 per wave)
+constexpr int kQTile = 64;        // dK/dV kernel: query rows per streamed tile
+constexpr int kQPerWG = 128;      // dQ kernel: queries per work-group (32 per wave)
+constexpr int kKTile = 64;        // dQ kernel: key rows per streamed tile
+
+template <int D>
+DEVI void store_acc_T(bf16_t* dst_row, const f32x16 (&acc)[D / 32], float scale, int h) {
+  // acc[db][i] = X^T[d = 32db + 8(i/4) + 4h + (i%4)][row of this lane]; 4 consecutive d -> 8 bytes
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 o4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o4[e] = (bf16_t)(acc[db][4 * g + e] * scale);
+      *reinterpret_cast<bf16x4*>(dst_row + 32 * db + 8 * g + 4 * h) = o4;
+    }
+}
+
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, int N, float alpha) {
+  constexpr int TILE_BYTES = kQTile * D * 2;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  // layout: Q buffers [2][TILE_BYTES], dO buffers [2][TILE_BYTES], L2 [2][64] float, delta [2][64] float
+  char* ldsQ = smem;
+  char* ldsdO = smem + 2 * TILE_BYTES;
+  float* ldsL = reinterpret_cast<float*>(smem + 4 * TILE_BYTES);
+  float* ldsD = ldsL + 2 * kQTile;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int r = lane & 31, h = lane >> 5;
+
+  const int nkt = N / kKeysPerWG;
+  const int wg = xcd_remap(blockIdx.x, gridDim.x);
+  const int bh = wg / nkt;
+  const int kt = wg % nkt;                         // early key blocks see the most queries: heavy first
+  const int k0 = kt * kKeysPerWG;
+  const int kw = k0 + 32 * wave;
+  const size_t head_off = (size_t)bh * N * D;
+  const bf16_t* Qh = Q + head_off;
+  const bf16_t* dOh = dO + head_off;
+  const float* Lh = LSE + (size_t)bh * N;
+  const float* Dh = delta + (size_t)bh * N;
+
+  // K_j^T / V_j^T fragments (B operands): lane (r,h) holds K[kw + r][16kc + 8h .. +7]
+  bf16x8 kf[D / 16], vf[D / 16];
+#pragma unroll
+  for (int kc = 0; kc < D / 16; ++kc) {
+    kf[kc] = *reinterpret_cast<const bf16x8*>(K + head_off + (size_t)(kw + r) * D + 16 * kc + 8 * h);
+    vf[kc] = *reinterpret_cast<const bf16x8*>(V + head_off + (size_t)(kw + r) * D + 16 * kc + 8 * h);
+  }
+  f32x16 dVt[D / 32], dKt[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { dVt[db][i] = 0.f; dKt[db][i] = 0.f; }
+
+  const int t0 = CAUSAL ? k0 / kQTile : 0;         // first query tile that sees any key of this block
+  const int nt = N / kQTile;
+  const float c2 = alpha * kLog2e;
+
+  TileRegs<D> qr, dor;
+  float lreg = 0.f, dreg = 0.f;
+  auto load_tile = [&](int t) {
+    tile_load_global<D>(qr, Qh + (size_t)t * kQTile * D, tid);
+    tile_load_global<D>(dor, dOh + (size_t)t * kQTile * D, tid);
+    if (tid < kQTile) lreg = Lh[t * kQTile + tid] * kLog2e;
+    else if (tid < 2 * kQTile) dreg = Dh[t * kQTile + tid - kQTile];
+  };
+  auto store_tile = [&](int buf) {
+    tile_store_lds<D>(qr, ldsQ + buf * TILE_BYTES, tid);
+    tile_store_lds<D>(dor, ldsdO + buf * TILE_BYTES, tid);
+    if (tid < kQTile) ldsL[buf * kQTile + tid] = lreg;
+    else if (tid < 2 * kQTile) ldsD[buf * kQTile + tid - kQTile] = dreg;
+  };
+  load_tile(t0);
+  store_tile(0);
+  __syncthreads();
+
+  for (int t = t0; t < nt; ++t) {
+    const int buf = (t - t0) & 1;
+    const char* tQ = ldsQ + buf * TILE_BYTES;
+    const char* tdO = ldsdO + buf * TILE_BYTES;
+    const float* tL = ldsL + buf * kQTile;
+    const float* tD = ldsD + buf * kQTile;
+    const bool has_next = (t + 1 < nt);
+    if (has_next) load_tile(t + 1);
+    const int qt0 = t * kQTile;
+#pragma unroll
+    for (int qb = 0; qb < kQTile / 32; ++qb) {
+      const int qb0 = qt0 + 32 * qb;
+      if (CAUSAL && (qb0 + 31 < kw)) continue;     // every query of the block precedes every key of the wave
+      // ---- S = Q_i K_j^T and dP = dO_i V_j^T (Alg. 2 steps 8, 11); rows = queries, lane = key
+      f32x16 s, dp;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+#pragma unroll
+      for (int kc = 0; kc < D / 16; ++kc) {
+        bf16x8 aq = lds_read_row8<D>(tQ, 32 * qb + r, 16 * kc + 8 * h);
+        s = mfma32(aq, kf[kc], s);
+        bf16x8 ado = lds_read_row8<D>(tdO, 32 * qb + r, 16 * kc + 8 * h);
+        dp = mfma32(ado, vf[kc], dp);
+      }
+      // ---- P = exp(S - L) (step 9), dS = P o (dP - delta) (step 12)
+      bf16x8 pf[2], dsf[2];
+      const bool diag = CAUSAL && (qb0 < kw + 31);
+      const int key = kw + r;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(tL + 32 * qb + 8 * g + 4 * h);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(tD + 32 * qb + 8 * g + 4 * h);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * g + e;
+          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l4[e]));
+          if (diag) {
+            int q = qb0 + 8 * g + 4 * h + e;
+            if (key > q) p = 0.f;
+          }
+          float ds = p * (dp[i] - d4[e]);
+          pf[i >> 3][i & 7] = (bf16_t)p;
+          dsf[i >> 3][i & 7] = (bf16_t)ds;
+        }
+      }
+      // ---- dV_j^T += dO_i^T P ,  dK_j^T += Q_i^T dS  (steps 10, 14)
+#pragma unroll
+      for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) {
+          bf16x8 a1 = lds_read_col8<D>(tdO, 32 * qb + 16 * cc, 32 * db, lane);
+          dVt[db] = mfma32(a1, pf[cc], dVt[db]);
+          bf16x8 a2 = lds_read_col8<D>(tQ, 32 * qb + 16 * cc, 32 * db, lane);
+          dKt[db] = mfma32(a2, dsf[cc], dKt[db]);
+        }
+    }
+    if (has_next) store_tile(buf ^ 1);
+    __syncthreads();
+  }
+  store_acc_T<D>(dV + head_off + (size_t)(kw + r) * D, dVt, 1.0f, h);
+  store_acc_T<D>(dK + head_off + (size_t)(kw + r) * D, dKt, alpha, h);
+}
+
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    bf16_t* __restrict__ dQ, int N, float alpha) {
+  constexpr int TILE_BYTES = kKTile * D * 2;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  char* ldsK = smem;
+  char* ldsV = smem + 2 * TILE_BYTES;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int r = lane & 31, h = lane >> 5;
+
+  const int nqt = N / kQPerWG;
+  const int wg = xcd_remap(blockIdx.x, gridDim.x);
+  const int bh = wg / nqt;
+  const int qt = nqt - 1 - (wg % nqt);
+  const int q0 = qt * kQPerWG;
+  const int qw = q0 + 32 * wave;
+  const size_t head_off = (size_t)bh * N * D;
+  const bf16_t* Kh = K + head_off;
+  const bf16_t* Vh = V + head_off;
+
+  // Q_i^T / dO_i^T fragments (B operands): lane (r,h) holds Q[qw + r][16kc + 8h .. +7]
+  bf16x8 qf[D / 16], dof[D / 16];
+#pragma unroll
+  for (int kc = 0; kc < D / 16; ++kc) {
+    qf[kc] = *reinterpret_cast<const bf16x8*>(Q + head_off + (size_t)(qw + r) * D + 16 * kc + 8 * h);
+    dof[kc] = *reinterpret_cast<const bf16x8*>(dO + head_off + (size_t)(qw + r) * D + 16 * kc + 8 * h);
+  }
+  const float l2 = LSE[(size_t)bh * N + qw + r] * kLog2e;
+  const float dl = delta[(size_t)bh * N + qw + r];
+  f32x16 dQt[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) dQt[db][i] = 0.f;
+
+  const int ntiles = CAUSAL ? (q0 + kQPerWG) / kKTile : N / kKTile;
+  const float c2 = alpha * kLog2e;
+
+  TileRegs<D> kr, vr;
+  tile_load_global<D>(kr, Kh, tid);
+  tile_load_global<D>(vr, Vh, tid);
+  tile_store_lds<D>(kr, ldsK, tid);
+  tile_store_lds<D>(vr, ldsV, tid);
+  __syncthreads();
+
+  for (int j = 0; j < ntiles; ++j) {
+    const int buf = j & 1;
+    const char* tK = ldsK + buf * TILE_BYTES;
+    const char* tV = ldsV + buf * TILE_BYTES;
+    const bool has_next = (j + 1 < ntiles);
+    if (has_next) {
+      tile_load_global<D>(kr, Kh + (size_t)(j + 1) * kKTile * D, tid);
+      tile_load_global<D>(vr, Vh + (size_t)(j + 1) * kKTile * D, tid);
+    }
+    const int kt0 = j * kKTile;
+    if (!CAUSAL || (kt0 <= qw + 31)) {
+#pragma unroll
+      for (int kb = 0; kb < kKTile / 32; ++kb) {
+        const int kb0 = kt0 + 32 * kb;
+        if (CAUSAL && (kb0 > qw + 31)) continue;   // every key of the block follows every query of the wave
+        // ---- S^T = K_j Q_i^T, dP^T = V_j dO_i^T ; rows = keys, lane = query
+        f32x16 s, dp;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+#pragma unroll
+        for (int kc = 0; kc < D / 16; ++kc) {
+          bf16x8 ak = lds_read_row8<D>(tK, 32 * kb + r, 16 * kc + 8 * h);
+          s = mfma32(ak, qf[kc], s);
+          bf16x8 av = lds_read_row8<D>(tV, 32 * kb + r, 16 * kc + 8 * h);
+          dp = mfma32(av, dof[kc], dp);
+        }
+        bf16x8 dsf[2];
+        const bool diag = CAUSAL && (kb0 + 31 > qw);
+        const int q = qw + r;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l2));
+          if (diag) {
+            int key = kb0 + 8 * (i >> 2) + 4 * h + (i & 3);
+            if (key > q) p = 0.f;
+          }
+          dsf[i >> 3][i & 7] = (bf16_t)(p * (dp[i] - dl));
+        }
+        // ---- dQ_i^T += K_j^T dS^T (step 13)
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db) {
+            bf16x8 a = lds_read_col8<D>(tK, 32 * kb + 16 * cc, 32 * db, lane);
+            dQt[db] = mfma32(a, dsf[cc], dQt[db]);
+          }
+      }
+    }
+    if (has_next) {
+      tile_store_lds<D>(kr, ldsK + (buf ^ 1) * TILE_BYTES, tid);
+      tile_store_lds<D>(vr, ldsV + (buf ^ 1) * TILE_BYTES, tid);
+    }
+    __syncthreads();
+  }
+  store_acc_T<D>(dQ + head_off + (size_t)(qw + r) * D, dQt, alpha, h);
+}
+
+template <typename KernT>
+static hipError_t set_smem(KernT kern, int smem, bool& done) {
+  if (done) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  if (e == hipSuccess) done = true;
+  return e;
+}
+
+template <int D, bool CAUSAL>
+static hipError_t launch_dkdv(const void* Q, const void* K, const void* V, const void* dO,
+                              const float* LSE, const float* delta, void* dK, void* dV, int BH,
+                              int N, float alpha, hipStream_t st) {
+  constexpr int smem = 4 * kQTile * D * 2 + 4 * kQTile * (int)sizeof(float);
+  static bool set = false;
+  auto k = attn_bwd_dkdv_kernel<D, CAUSAL>;
+  hipError_t e;
+  if ((e = set_smem(k, smem, set)) != hipSuccess) return e;
+  hipLaunchKernelGGL(k, dim3(BH * (N / kKeysPerWG)), dim3(256), smem, st, (const bf16_t*)Q,
+                     (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
+                     (bf16_t*)dK, (bf16_t*)dV, N, alpha);
+  return hipGetLastError();
+}
+
+template <int D, bool CAUSAL>
+static hipError_t launch_dq(const void* Q, const void* K, const void* V, const void* dO,
+                            const float* LSE, const float* delta, void* dQ, int BH, int N,
+                            float alpha, hipStream_t st) {
+  constexpr int smem = 4 * kKTile * D * 2;
+  static bool set = false;
+  auto k = attn_bwd_dq_kernel<D, CAUSAL>;
+  hipError_t e;
+  if ((e = set_smem(k, smem, set)) != hipSuccess) return e;
+  hipLaunchKernelGGL(k, dim3(BH * (N / kQPerWG)), dim3(256), smem, st, (const bf16_t*)Q,
+                     (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
+                     (bf16_t*)dQ, N, alpha);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t attn_bwd_dkdv_dispatch(const void* Q, const void* K, const void* V, const void* dO,
+                                  const float* LSE, const float* delta, void* dK, void* dV,
+                                  int BH, int N, int d, int causal, float alpha, hipStream_t st) {
+  if (d == 64) return causal ? launch_dkdv<64, true>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, st)
+                             : launch_dkdv<64, false>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, st);
+  if (d == 128) return causal ? launch_dkdv<128, true>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, st)
+                              : launch_dkdv<128, false>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, st);
+  return hipErrorInvalidValue;
+}
+
+hipError_t attn_bwd_dq_dispatch(const void* Q, const void* K, const void* V, const void* dO,
+                                const float* LSE, const float* delta, void* dQ, int BH, int N,
+                                int d, int causal, float alpha, hipStream_t st) {
+  if (d == 64) return causal ? launch_dq<64, true>(Q, K, V, dO, LSE, delta, dQ, BH, N, alpha, st)
+                             : launch_dq<64, false>(Q, K, V, dO, LSE, delta, dQ, BH, N, alpha, st);
+  if (d == 128) return causal ? launch_dq<128, true>(Q, K, V, dO, LSE, delta, dQ, BH, N, alpha, st)
+                              : launch_dq<128, false>(Q, K, V, dO, LSE, delta, dQ, BH, N, alpha, st);
+  return hipErrorInvalidValue;
+}

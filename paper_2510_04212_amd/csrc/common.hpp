@@ -1,0 +1,131 @@
+// Shared device helpers for the gfx950 attention kernels: vector types, the matrix-core
+// wrappers, the LDS tile layout (16-byte-chunk XOR swizzle) and cross-lane exchanges.
+//
+// Matrix-core fragment layouts used throughout (wave64, v_mfma_f32_32x32x16_bf16,
+// D[32x32] += A[32x16] * B[16x32]; lane l, r = l & 31, h = l >> 5):
+//   A operand: lane holds A[r][8h .. 8h+7]            (8 consecutive k of one row)
+//   B operand: lane holds B[8h .. 8h+7][r]            (8 consecutive k of one column)
+//   D / C    : register i of lane holds D[8*(i/4) + 4h + (i%4)][r]
+// Because the contraction index may be permuted freely as long as A and B agree, a C-layout
+// tile can be fed back as a B operand: registers 8c..8c+7 of a lane are the k-slots (h, 0..7)
+// of 16-wide k-chunk c, i.e. k-slot (h, j) of chunk c  <->  tile row 16c + 8*(j/4) + 4h + (j%4).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+#define DEVI __device__ __forceinline__
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+DEVI f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Swizzle of the 16-byte chunk index inside one tile row, chosen so that (a) 16 lanes reading
+// the same chunk of 16 consecutive rows and (b) a transposing read touching 8 consecutive rows
+// x 64 bytes both spread over all 64 LDS banks.
+template <int D> DEVI int swz(int row);
+template <> DEVI int swz<128>(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+template <> DEVI int swz<64>(int row) {
+  int t = row >> 1;
+  return ((t & 1) << 2) | (t & 2) | ((t >> 2) & 1);
+}
+
+// Byte offset of element (row, col) of a [rows][D] bf16 tile in LDS; col must be a multiple of 4
+// for 8-byte accesses and of 8 for 16-byte accesses.
+template <int D> DEVI int tile_off(int row, int col) {
+  int chunk = col >> 3;
+  return row * (D * 2) + ((chunk ^ swz<D>(row)) << 4) + ((col & 7) << 1);
+}
+
+// 16-byte natural read: 8 consecutive columns of one row (an A/B fragment whose contraction
+// index runs along the tile's columns).
+template <int D> DEVI bf16x8 lds_read_row8(const char* tile, int row, int col) {
+  return *reinterpret_cast<const bf16x8*>(tile + tile_off<D>(row, col));
+}
+
+// Transposing read: returns, for this lane, 4 consecutive ROWS (row0..row0+3) of column
+// col0 + (lane & 15).  ds_read_b64_tr_b16 works on groups of 16 lanes: lane i of a group
+// supplies the address of 4 consecutive columns (4*(i&3)..) of row (i>>2), and receives
+// column i of rows 0..3.  col0 must be a multiple of 16.
+template <int D> DEVI s16x4 lds_read_tr4(const char* tile, int row0, int col0, int lane) {
+  int i = lane & 15;
+  int off = tile_off<D>(row0 + (i >> 2), col0 + ((i & 3) << 2));
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + off));
+}
+
+// Fragment whose contraction index runs along the tile's ROWS: k-slots (h, 0..7) of the
+// 16-row chunk starting at row_base are rows row_base + 8*(j/4) + 4h + (j%4), j = 0..7;
+// the lane's own index (lane & 31) selects column col_base + (lane & 31).
+template <int D> DEVI bf16x8 lds_read_col8(const char* tile, int row_base, int col_base, int lane) {
+  int h = lane >> 5;
+  int c0 = col_base + (lane & 16);
+  union { struct { s16x4 lo, hi; } p; bf16x8 v; } u;
+  u.p.lo = lds_read_tr4<D>(tile, row_base + 4 * h, c0, lane);
+  u.p.hi = lds_read_tr4<D>(tile, row_base + 8 + 4 * h, c0, lane);
+  return u.v;
+}
+
+// Value held by the lane 32 positions away (lane ^ 32).
+DEVI float partner32(float x) {
+  unsigned u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  // r[0] = {lower-half values in all lanes}, r[1] = {upper-half values in all lanes}
+  return (threadIdx.x & 32) ? __uint_as_float(r[0]) : __uint_as_float(r[1]);
+}
+DEVI float max_with_partner32(float x) {
+  unsigned u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+DEVI float sum_with_partner32(float x) {
+  unsigned u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+DEVI float bf16_bits_to_float(unsigned short b) { return __uint_as_float(((unsigned)b) << 16); }
+
+// Cooperative copy of a 64-row x D bf16 tile: global -> registers, registers -> swizzled LDS.
+// 256 threads, each moving D/32 16-byte chunks; consecutive threads take consecutive chunks.
+template <int D> struct TileRegs { u32x4 v[D / 32]; };
+
+template <int D> DEVI void tile_load_global(TileRegs<D>& r, const bf16_t* src_row0, int tid) {
+  constexpr int CH = D / 8;
+#pragma unroll
+  for (int i = 0; i < D / 32; ++i) {
+    int id = tid + 256 * i;
+    int row = id / CH, c = id % CH;
+    r.v[i] = *reinterpret_cast<const u32x4*>(src_row0 + (size_t)row * D + c * 8);
+  }
+}
+template <int D> DEVI void tile_store_lds(const TileRegs<D>& r, char* tile, int tid) {
+  constexpr int CH = D / 8;
+#pragma unroll
+  for (int i = 0; i < D / 32; ++i) {
+    int id = tid + 256 * i;
+    int row = id / CH, c = id % CH;
+    *reinterpret_cast<u32x4*>(tile + tile_off<D>(row, c * 8)) = r.v[i];
+  }
+}
+
+// Work-group index remap: consecutive hardware work-group ids go round-robin over the 8 XCDs
+// (each with its own L2).  Give every XCD a contiguous range of logical ids so that the
+// work-groups sharing one head's K/V run on the same L2.  Only applied when the grid is a
+// multiple of 8 (otherwise the map would not be a bijection).
+DEVI int xcd_remap(int id, int n) {
+  if ((n & 7) != 0) return id;
+  return (id & 7) * (n >> 3) + (id >> 3);
+}

@@ -1,0 +1,230 @@
+// Flash-attention forward for gfx950: Alg. 1 (standard safe softmax) and Alg. 3 (stabilised
+// normaliser, Sec. 4) of arXiv 2510.04212, one work-group per (batch, head, 128-query block).
+//
+// Work split: 4 waves, each owning 32 query rows; key tiles of B_c = 64 rows of K and V are
+// staged in LDS (double buffered) and shared by the 4 waves.  Per tile a wave computes
+//     S^T[key][query] = K_j Q_i^T           (A = K_j from LDS, B = Q_i^T held in registers)
+// so that one query row lives in lane r and lane r+32; row max / row sum / near-max count are
+// in-register reductions plus one exchange with the partner lane.  P-bar^T in the accumulator
+// layout is directly the B operand of
+//     O^T[d][query] += V_j^T P-bar^T          (A = V_j^T via transposing LDS reads)
+// which keeps the per-query rescale factor uniform over a lane's accumulator registers.
+#include "common.hpp"
+
+namespace {
+
+constexpr int kBr = 128;   // query rows per work-group
+constexpr int kBc = 64;    // key rows per tile
+
+template <int D, bool CAUSAL, int VARIANT>
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    bf16_t* __restrict__ O, float* __restrict__ LSE, int N, float alpha, float beta, float eps) {
+  constexpr int TILE_BYTES = kBc * D * 2;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  // layout: K buffers [2][TILE_BYTES], then V buffers [2][TILE_BYTES]
+  char* ldsK = smem;
+  char* ldsV = smem + 2 * TILE_BYTES;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int r = lane & 31, h = lane >> 5;
+
+  const int nqt = N / kBr;
+  const int wg = xcd_remap(blockIdx.x, gridDim.x);
+  const int bh = wg / nqt;
+  const int qt = nqt - 1 - (wg % nqt);          // heavy (late) query blocks first under the causal mask
+  const int q0 = qt * kBr;
+  const int qw = q0 + 32 * wave;                 // first query row of this wave
+  const size_t head_off = (size_t)bh * N * D;
+  const bf16_t* Qh = Q + head_off;
+  const bf16_t* Kh = K + head_off;
+  const bf16_t* Vh = V + head_off;
+
+  // Q_i^T fragments: lane (r,h) holds Q[qw + r][16kc + 8h .. +7] for every kc.
+  bf16x8 qf[D / 16];
+#pragma unroll
+  for (int kc = 0; kc < D / 16; ++kc)
+    qf[kc] = *reinterpret_cast<const bf16x8*>(Qh + (size_t)(qw + r) * D + 16 * kc + 8 * h);
+
+  f32x16 acc[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
+
+  float m = -INFINITY;      // running normaliser, natural-log units of the alpha-scaled scores
+  float lsum = 0.f;         // this lane's share of the running row sum (its 32 of the 64 keys per tile)
+
+  const int ntiles = CAUSAL ? (q0 + kBr) / kBc : N / kBc;
+  const float c2 = alpha * kLog2e;
+
+  TileRegs<D> kr, vr;
+  tile_load_global<D>(kr, Kh, tid);
+  tile_load_global<D>(vr, Vh, tid);
+  tile_store_lds<D>(kr, ldsK, tid);
+  tile_store_lds<D>(vr, ldsV, tid);
+  __syncthreads();
+
+  for (int j = 0; j < ntiles; ++j) {
+    const int buf = j & 1;
+    const char* tK = ldsK + buf * TILE_BYTES;
+    const char* tV = ldsV + buf * TILE_BYTES;
+    const bool has_next = (j + 1 < ntiles);
+    if (has_next) {
+      tile_load_global<D>(kr, Kh + (size_t)(j + 1) * kBc * D, tid);
+      tile_load_global<D>(vr, Vh + (size_t)(j + 1) * kBc * D, tid);
+    }
+    const int k0 = j * kBc;
+    // A wave whose 32 rows all lie above this key tile has nothing to do in it (causal).
+    const bool active = !CAUSAL || (k0 <= qw + 31);
+    if (active) {
+      // ---- S^T = K_j Q_i^T (Alg. 1 step 6); raw scores, alpha not yet applied
+      f32x16 s[2];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
+#pragma unroll
+      for (int kc = 0; kc < D / 16; ++kc) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          bf16x8 a = lds_read_row8<D>(tK, 32 * kb + r, 16 * kc + 8 * h);
+          s[kb] = mfma32(a, qf[kc], s[kb]);
+        }
+      }
+      // ---- causal mask: key > query -> -inf (only tiles that cross the diagonal)
+      if (CAUSAL && (k0 + kBc - 1 > qw)) {
+        const int q = qw + r;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            int key = k0 + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
+            if (key > q) s[kb][i] = -INFINITY;
+          }
+      }
+      // ---- tile row maximum r_m (of the alpha-scaled scores)
+      float mx = s[0][0];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
+      mx = max_with_partner32(mx);
+      const float r_m = mx * alpha;
+      float m_prime = r_m;
+      if (VARIANT == 1) {
+        // Alg. 3: r_s = #{ r_m - S <= eps } over the tile row; a repeated maximum moves the
+        // normaliser to beta*r_m (r_m > 0) or to 0 (r_m < 0).
+        float cnt = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            s[kb][i] *= alpha;                       // from here on s holds alpha-scaled scores
+            cnt += ((r_m - s[kb][i]) <= eps) ? 1.f : 0.f;
+          }
+        cnt = sum_with_partner32(cnt);
+        const bool repeated = cnt > 1.5f;
+        m_prime = (repeated && r_m > 0.f) ? beta * r_m : r_m;
+        m_prime = (repeated && r_m < 0.f) ? 0.f : m_prime;
+      }
+      const float m_new = fmaxf(m, m_prime);         // Alg. 1 step 7 / Alg. 3
+      const float corr = __builtin_amdgcn_exp2f((m - m_new) * kLog2e);
+      m = m_new;
+      const float mneg = -m_new * kLog2e;
+      // ---- P-bar = exp(S - m), rounded to bf16; row sum of the ROUNDED values
+      bf16x8 pf[2][2];
+      float psum = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+          for (int jj = 0; jj < 8; ++jj) {
+            float x = s[kb][8 * cc + jj];
+            float t = (VARIANT == 1) ? __builtin_fmaf(x, kLog2e, mneg) : __builtin_fmaf(x, c2, mneg);
+            float p = __builtin_amdgcn_exp2f(t);
+            bf16_t pb = (bf16_t)p;
+            pf[kb][cc][jj] = pb;
+            psum += (float)pb;
+          }
+      lsum = lsum * corr + psum;
+      // ---- O^T <- diag(corr) O^T + V_j^T P-bar^T (Alg. 1 step 8)
+      if (__builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc[db][i] *= corr;
+      }
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db) {
+            bf16x8 a = lds_read_col8<D>(tV, 32 * kb + 16 * cc, 32 * db, lane);
+            acc[db] = mfma32(a, pf[kb][cc], acc[db]);
+          }
+    }
+    if (has_next) {
+      tile_store_lds<D>(kr, ldsK + (buf ^ 1) * TILE_BYTES, tid);
+      tile_store_lds<D>(vr, ldsV + (buf ^ 1) * TILE_BYTES, tid);
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue (Alg. 1 steps 10-13).  Rounding points of Sec. 3.3.2: the unnormalised
+  // output is rounded to bf16 first, then divided by l, then rounded again.
+  const float l = sum_with_partner32(lsum);
+  bf16_t* Oq = O + head_off + (size_t)(qw + r) * D;
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 o4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        bf16_t obar = (bf16_t)acc[db][4 * g + e];
+        o4[e] = (bf16_t)((float)obar / l);
+      }
+      *reinterpret_cast<bf16x4*>(Oq + 32 * db + 8 * g + 4 * h) = o4;
+    }
+  if (h == 0) LSE[(size_t)bh * N + qw + r] = m + __logf(l);
+}
+
+}  // namespace
+
+extern "C" int attn_fwd_key_tile(int d) { return (d == 64 || d == 128) ? kBc : 0; }
+
+template <int D, bool CAUSAL, int VARIANT>
+static hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                             int BH, int N, float alpha, float beta, float eps, hipStream_t st) {
+  constexpr int smem = 4 * kBc * D * 2;
+  static bool attr_set = false;
+  auto kern = attn_fwd_kernel<D, CAUSAL, VARIANT>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  dim3 grid(BH * (N / kBr));
+  hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, (const bf16_t*)Q, (const bf16_t*)K,
+                     (const bf16_t*)V, (bf16_t*)O, LSE, N, alpha, beta, eps);
+  return hipGetLastError();
+}
+
+// Host-side dispatch used by the C ABI (api.hip).  Shapes are validated by the caller.
+hipError_t attn_fwd_dispatch(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                             int BH, int N, int d, int causal, float alpha, int variant,
+                             float beta, float eps, hipStream_t st) {
+#define CASE(DD, CC, VV)                                                                     \
+  if (d == DD && (causal != 0) == CC && variant == VV)                                        \
+    return launch_fwd<DD, CC, VV>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, st);
+  CASE(64, false, 0) CASE(64, false, 1) CASE(64, true, 0) CASE(64, true, 1)
+  CASE(128, false, 0) CASE(128, false, 1) CASE(128, true, 0) CASE(128, true, 1)
+#undef CASE
+  return hipErrorInvalidValue;
+}

@@ -1,0 +1,85 @@
+"""CPU-only checks of the boundary: the library loads, exports every symbol the header declares,
+and its host-side validation rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2510_04212_amd import binding as b
+    return b
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(attn_[a-z_]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported(binding):
+    declared = _declared_functions()
+    assert set(declared) == set(binding.EXPORTS)
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(binding):
+    for st in range(6):
+        s = binding.status_string(st)
+        assert s and "unknown" not in s
+    assert "unknown" in binding.status_string(99)
+
+
+def test_key_tile_and_workspace_queries(binding):
+    assert binding.fwd_key_tile(64) == 64 and binding.fwd_key_tile(128) == 64
+    assert binding.fwd_key_tile(96) == 0
+    assert binding.bwd_workspace_bytes(4, 32, 4096, 128) == 4 * 32 * 4096 * 4
+    assert binding.bwd_workspace_bytes(1, 1, 128, 64) == 512          # rounded up to 256
+    assert binding.bwd_workspace_bytes(1, 1, 100, 64) == 0            # unsupported shape
+    assert binding.bwd_workspace_bytes(0, 4, 128, 64) == 0
+
+
+def test_argument_validation_happens_on_the_host(binding):
+    """None of these calls reaches a kernel launch (no GPU is needed to run them)."""
+    lib = binding.raw()
+    OK, NULL, BAD, UNSUP, WS = 0, 1, 2, 3, 4
+    p = ctypes.c_void_p(0x1000)          # a non-NULL, aligned fake pointer: never dereferenced
+    mis = ctypes.c_void_p(0x1004)
+    fwd = lambda Q, K, V, O, L, B, H, N, d, var=0, scale=0.125: lib.attn_fwd(Q, K, V, O, L, B, H, N, d, 1, scale, var, None)
+    assert fwd(p, p, p, p, p, 1, 1, 100, 64) == UNSUP        # N not a multiple of 128
+    assert fwd(p, p, p, p, p, 1, 1, 128, 96) == UNSUP        # head dim
+    assert fwd(p, p, p, p, p, 1, 1, 0, 64) == UNSUP
+    assert fwd(p, p, p, p, p, -1, 1, 128, 64) == BAD
+    assert fwd(p, p, p, p, p, 1, 1, 128, 64, var=2) == BAD
+    assert fwd(p, p, p, p, p, 1, 1, 128, 64, scale=0.0) == BAD
+    assert fwd(None, p, p, p, p, 1, 1, 128, 64) == NULL
+    assert fwd(p, p, p, p, None, 1, 1, 128, 64) == NULL
+    assert fwd(mis, p, p, p, p, 1, 1, 128, 64) == BAD
+    q = ctypes.c_void_p(0x2000)
+    assert fwd(q, p, p, q, p, 1, 1, 128, 64) == BAD          # O aliases Q
+    assert fwd(None, None, None, None, None, 0, 5, 128, 64) == OK      # empty batch: no-op
+    ex = lambda beta, eps: lib.attn_fwd_ex(q, p, p, p, p, 1, 1, 128, 64, 1, 0.125, 1, beta, eps, None)
+    assert ex(1.0, 1e-3) == BAD and ex(2.0, -1.0) == BAD and ex(float("nan"), 1e-3) == BAD
+    assert lib.attn_delta(None, p, p, 1, 1, 128, 64, None) == NULL
+    assert lib.attn_delta(p, p, p, 1, 1, 130, 64, None) == UNSUP
+    assert lib.attn_delta(None, None, None, 2, 0, 128, 64, None) == OK
+    ptrs = [ctypes.c_void_p(0x1000 * (i + 1)) for i in range(9)]
+    ws = ctypes.c_void_p(0x100000)
+    bwd = lambda a, w, wb, N=128: lib.attn_bwd(*a, w, wb, 1, 1, N, 64, 1, 0.125, 0, None)
+    assert bwd(ptrs, ws, 0) == WS                            # too small
+    assert bwd(ptrs, ctypes.c_void_p(0x100010), 4096) == WS  # not 256-byte aligned
+    assert bwd(ptrs, None, 4096) == NULL
+    assert bwd(ptrs, ws, 4096, N=64) == UNSUP
+    alias = list(ptrs); alias[6] = alias[0]
+    assert bwd(alias, ws, 4096) == BAD                       # dQ aliases Q
+    alias = list(ptrs); alias[7] = alias[8]
+    assert bwd(alias, ws, 4096) == BAD                       # dK aliases dV
+    nul = list(ptrs); nul[5] = None
+    assert bwd(nul, ws, 4096) == NULL

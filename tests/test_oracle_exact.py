@@ -165,3 +165,16 @@ def test_bh_wrapper_selects_heads():
     O, L, dQ, dK, dV, delta = exact.forward_backward(Q[1, 2], K[1, 2], V[1, 2], dO[1, 2], 0.5, True)
     assert np.array_equal(out["O"][1, 2], O) and np.array_equal(out["dK"][1, 2], dK)
     assert np.isnan(out["O"][0, 0]).all()
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("row_block", [None, 1, 7, 16])
+def test_forward_backward_slabs_equal_separate_functions(causal, row_block):
+    """forward_backward() (optionally visiting query rows in slabs) must reproduce forward() and
+    backward(), which the tests above pin."""
+    Q, K, V, dO = _rand(51, 37, 5)
+    O, L = exact.forward(Q, K, V, 0.4, causal)
+    dQ, dK, dV, delta = exact.backward(Q, K, V, dO, 0.4, causal)
+    got = exact.forward_backward(Q, K, V, dO, 0.4, causal, row_block=row_block)
+    for a, b in zip(got, (O, L, dQ, dK, dV, delta)):
+        assert np.max(np.abs(a - b)) < 1e-13
