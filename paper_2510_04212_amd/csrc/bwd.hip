@@ -88,22 +88,22 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
   const int nt = N / kQTile;
   const float c2 = alpha * kLog2e;
 
-  TileRegs<D> qr, dor;
-  float lreg = 0.f, dreg = 0.f;
-  auto load_tile = [&](int t) {
-    tile_load_global<D>(qr, Qh + (size_t)t * kQTile * D, tid);
-    tile_load_global<D>(dor, dOh + (size_t)t * kQTile * D, tid);
-    if (tid < kQTile) lreg = Lh[t * kQTile + tid] * kLog2e;
-    else if (tid < 2 * kQTile) dreg = Dh[t * kQTile + tid - kQTile];
+  // Q_i / dO_i tiles go global -> LDS asynchronously; L_i (pre-multiplied by log2 e) and delta_i
+  // (64 floats each) pass through one register of threads 0..127.
+  float sreg = 0.f;
+  auto load_tile = [&](int t, int buf) {
+    tile_load_async<D>(ldsQ + buf * TILE_BYTES, Qh + (size_t)t * kQTile * D, tid);
+    tile_load_async<D>(ldsdO + buf * TILE_BYTES, dOh + (size_t)t * kQTile * D, tid);
+    if (tid < kQTile) sreg = Lh[t * kQTile + tid] * kLog2e;
+    else if (tid < 2 * kQTile) sreg = Dh[t * kQTile + tid - kQTile];
   };
-  auto store_tile = [&](int buf) {
-    tile_store_lds<D>(qr, ldsQ + buf * TILE_BYTES, tid);
-    tile_store_lds<D>(dor, ldsdO + buf * TILE_BYTES, tid);
-    if (tid < kQTile) ldsL[buf * kQTile + tid] = lreg;
-    else if (tid < 2 * kQTile) ldsD[buf * kQTile + tid - kQTile] = dreg;
+  auto store_stats = [&](int buf) {
+    if (tid < kQTile) ldsL[buf * kQTile + tid] = sreg;
+    else if (tid < 2 * kQTile) ldsD[buf * kQTile + tid - kQTile] = sreg;
   };
-  load_tile(t0);
-  store_tile(0);
+  load_tile(t0, 0);
+  store_stats(0);
+  wait_vmem();
   __syncthreads();
 
   for (int t = t0; t < nt; ++t) {
@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
     const float* tL = ldsL + buf * kQTile;
     const float* tD = ldsD + buf * kQTile;
     const bool has_next = (t + 1 < nt);
-    if (has_next) load_tile(t + 1);
+    if (has_next) load_tile(t + 1, buf ^ 1);
     const int qt0 = t * kQTile;
 #pragma unroll
     for (int qb = 0; qb < kQTile / 32; ++qb) {
@@ -162,7 +162,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
           dKt[db] = mfma32(a2, dsf[cc], dKt[db]);
         }
     }
-    if (has_next) store_tile(buf ^ 1);
+    if (has_next) store_stats(buf ^ 1);
+    wait_vmem();
     __syncthreads();
   }
   store_acc_T<D>(dV + head_off + (size_t)(kw + r) * D, dVt, 1.0f, h);
@@ -212,11 +213,9 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
   const int ntiles = CAUSAL ? (q0 + kQPerWG) / kKTile : N / kKTile;
   const float c2 = alpha * kLog2e;
 
-  TileRegs<D> kr, vr;
-  tile_load_global<D>(kr, Kh, tid);
-  tile_load_global<D>(vr, Vh, tid);
-  tile_store_lds<D>(kr, ldsK, tid);
-  tile_store_lds<D>(vr, ldsV, tid);
+  tile_load_async<D>(ldsK, Kh, tid);
+  tile_load_async<D>(ldsV, Vh, tid);
+  wait_vmem();
   __syncthreads();
 
   for (int j = 0; j < ntiles; ++j) {
@@ -225,8 +224,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     const char* tV = ldsV + buf * TILE_BYTES;
     const bool has_next = (j + 1 < ntiles);
     if (has_next) {
-      tile_load_global<D>(kr, Kh + (size_t)(j + 1) * kKTile * D, tid);
-      tile_load_global<D>(vr, Vh + (size_t)(j + 1) * kKTile * D, tid);
+      tile_load_async<D>(ldsK + (buf ^ 1) * TILE_BYTES, Kh + (size_t)(j + 1) * kKTile * D, tid);
+      tile_load_async<D>(ldsV + (buf ^ 1) * TILE_BYTES, Vh + (size_t)(j + 1) * kKTile * D, tid);
     }
     const int kt0 = j * kKTile;
     if (!CAUSAL || (kt0 <= qw + 31)) {
@@ -267,10 +266,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
           }
       }
     }
-    if (has_next) {
-      tile_store_lds<D>(kr, ldsK + (buf ^ 1) * TILE_BYTES, tid);
-      tile_store_lds<D>(vr, ldsV + (buf ^ 1) * TILE_BYTES, tid);
-    }
+    wait_vmem();
     __syncthreads();
   }
   store_acc_T<D>(dQ + head_off + (size_t)(qw + r) * D, dQt, alpha, h);

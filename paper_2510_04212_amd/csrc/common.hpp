@@ -98,27 +98,39 @@ DEVI float sum_with_partner32(float x) {
 
 DEVI float bf16_bits_to_float(unsigned short b) { return __uint_as_float(((unsigned)b) << 16); }
 
-// Cooperative copy of a 64-row x D bf16 tile: global -> registers, registers -> swizzled LDS.
-// 256 threads, each moving D/32 16-byte chunks; consecutive threads take consecutive chunks.
-template <int D> struct TileRegs { u32x4 v[D / 32]; };
-
-template <int D> DEVI void tile_load_global(TileRegs<D>& r, const bf16_t* src_row0, int tid) {
-  constexpr int CH = D / 8;
+// Asynchronous copy of a 64-row x D bf16 tile from global memory straight into swizzled LDS
+// (global_load_lds_dwordx4: no registers are involved; completion is tracked by vmcnt).
+// One wave-instruction moves 64 x 16 bytes to LDS base + 16*lane, i.e. 1024 consecutive bytes =
+// 64/CH whole tile rows; the XOR swizzle is applied on the GLOBAL side: the lane that lands in
+// chunk slot s of row r fetches chunk s ^ swz(r) of that row.  256 threads (4 waves).
+// The caller must execute wait_vmem() and a barrier before any wave reads the tile.
+template <int D> DEVI void tile_load_async(char* tile, const bf16_t* src_row0, int tid) {
+  constexpr int CH = D / 8;                // 16-byte chunks per row
+  constexpr int RPI = 64 / CH;             // rows per wave-instruction
+  constexpr int NI = 64 / RPI / 4;         // instructions per wave
+  typedef __attribute__((address_space(3))) void lds_void;
+  typedef __attribute__((address_space(1))) const void glb_void;
+  const int wave = tid >> 6, lane = tid & 63;
 #pragma unroll
-  for (int i = 0; i < D / 32; ++i) {
-    int id = tid + 256 * i;
-    int row = id / CH, c = id % CH;
-    r.v[i] = *reinterpret_cast<const u32x4*>(src_row0 + (size_t)row * D + c * 8);
+  for (int i = 0; i < NI; ++i) {
+    const int rbase = (wave * NI + i) * RPI;
+    const int row = rbase + lane / CH;
+    const int c = (lane % CH) ^ swz<D>(row);
+    __builtin_amdgcn_global_load_lds((glb_void*)(src_row0 + (size_t)row * D + c * 8),
+                                     (lds_void*)(tile + rbase * (D * 2)), 16, 0, 0);
   }
 }
-template <int D> DEVI void tile_store_lds(const TileRegs<D>& r, char* tile, int tid) {
-  constexpr int CH = D / 8;
-#pragma unroll
-  for (int i = 0; i < D / 32; ++i) {
-    int id = tid + 256 * i;
-    int row = id / CH, c = id % CH;
-    *reinterpret_cast<u32x4*>(tile + tile_off<D>(row, c * 8)) = r.v[i];
-  }
+
+// s_waitcnt vmcnt(0): every outstanding global load (including loads into LDS) has landed.
+DEVI void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// Sum of the two bf16 values of a packed pair, added to acc in float32 (v_dot2c_f32_bf16 with
+// a (1,1) second operand).
+DEVI float add_pair_bf16(bf16x2 p, float acc) {
+  bf16x2 one;
+  one[0] = (bf16_t)1.0f;
+  one[1] = (bf16_t)1.0f;
+  return __builtin_amdgcn_fdot2_f32_bf16(p, one, acc, false);
 }
 
 // Work-group index remap: consecutive hardware work-group ids go round-robin over the 8 XCDs

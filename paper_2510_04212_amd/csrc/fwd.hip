@@ -60,11 +60,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
   const int ntiles = CAUSAL ? (q0 + kBr) / kBc : N / kBc;
   const float c2 = alpha * kLog2e;
 
-  TileRegs<D> kr, vr;
-  tile_load_global<D>(kr, Kh, tid);
-  tile_load_global<D>(vr, Vh, tid);
-  tile_store_lds<D>(kr, ldsK, tid);
-  tile_store_lds<D>(vr, ldsV, tid);
+  tile_load_async<D>(ldsK, Kh, tid);
+  tile_load_async<D>(ldsV, Vh, tid);
+  wait_vmem();
   __syncthreads();
 
   for (int j = 0; j < ntiles; ++j) {
@@ -72,9 +70,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
     const char* tK = ldsK + buf * TILE_BYTES;
     const char* tV = ldsV + buf * TILE_BYTES;
     const bool has_next = (j + 1 < ntiles);
-    if (has_next) {
-      tile_load_global<D>(kr, Kh + (size_t)(j + 1) * kBc * D, tid);
-      tile_load_global<D>(vr, Vh + (size_t)(j + 1) * kBc * D, tid);
+    if (has_next) {   // lands in the other buffer while this tile is being processed
+      tile_load_async<D>(ldsK + (buf ^ 1) * TILE_BYTES, Kh + (size_t)(j + 1) * kBc * D, tid);
+      tile_load_async<D>(ldsV + (buf ^ 1) * TILE_BYTES, Vh + (size_t)(j + 1) * kBc * D, tid);
     }
     const int k0 = j * kBc;
     // A wave whose 32 rows all lie above this key tile has nothing to do in it (causal).
@@ -142,13 +140,17 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
 #pragma unroll
         for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
-          for (int jj = 0; jj < 8; ++jj) {
-            float x = s[kb][8 * cc + jj];
-            float t = (VARIANT == 1) ? __builtin_fmaf(x, kLog2e, mneg) : __builtin_fmaf(x, c2, mneg);
-            float p = __builtin_amdgcn_exp2f(t);
-            bf16_t pb = (bf16_t)p;
-            pf[kb][cc][jj] = pb;
-            psum += (float)pb;
+          for (int jj = 0; jj < 8; jj += 2) {
+            bf16x2 pp;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+              float x = s[kb][8 * cc + jj + e];
+              float t = (VARIANT == 1) ? __builtin_fmaf(x, kLog2e, mneg) : __builtin_fmaf(x, c2, mneg);
+              pp[e] = (bf16_t)__builtin_amdgcn_exp2f(t);
+            }
+            pf[kb][cc][jj] = pp[0];
+            pf[kb][cc][jj + 1] = pp[1];
+            psum = add_pair_bf16(pp, psum);
           }
       lsum = lsum * corr + psum;
       // ---- O^T <- diag(corr) O^T + V_j^T P-bar^T (Alg. 1 step 8)
@@ -168,10 +170,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
             acc[db] = mfma32(a, pf[kb][cc], acc[db]);
           }
     }
-    if (has_next) {
-      tile_store_lds<D>(kr, ldsK + (buf ^ 1) * TILE_BYTES, tid);
-      tile_store_lds<D>(vr, ldsV + (buf ^ 1) * TILE_BYTES, tid);
-    }
+    wait_vmem();
     __syncthreads();
   }
 
