@@ -20,6 +20,8 @@
 // multiplies the float32 dQ / dK accumulators once; outputs are rounded to bf16 when stored.
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace {
 
 constexpr int kKeysPerWG = 128;   // dK/dV kernel: keys per work-group (32 per wave)
@@ -115,10 +117,10 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
     const bool has_next = (t + 1 < nt);
     if (has_next) load_tile(t + 1, buf ^ 1);
     const int qt0 = t * kQTile;
-#pragma unroll
-    for (int qb = 0; qb < kQTile / 32; ++qb) {
+    // one 32-query block against this wave's 32 keys; DIAG: the block crosses the diagonal
+    auto qblock = [&](auto diag_c, int qb) {
+      constexpr bool DIAG = decltype(diag_c)::value;
       const int qb0 = qt0 + 32 * qb;
-      if (CAUSAL && (qb0 + 31 < kw)) continue;     // every query of the block precedes every key of the wave
       // ---- S = Q_i K_j^T and dP = dO_i V_j^T (Alg. 2 steps 8, 11); rows = queries, lane = key
       f32x16 s, dp;
 #pragma unroll
@@ -130,9 +132,9 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
         bf16x8 ado = lds_read_row8<D>(tdO, 32 * qb + r, 16 * kc + 8 * h);
         dp = mfma32(ado, vf[kc], dp);
       }
+      sched_reads_ahead_of_mfma<D / 8, 1, 4>();
       // ---- P = exp(S - L) (step 9), dS = P o (dP - delta) (step 12)
       bf16x8 pf[2], dsf[2];
-      const bool diag = CAUSAL && (qb0 < kw + 31);
       const int key = kw + r;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -142,7 +144,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
         for (int e = 0; e < 4; ++e) {
           const int i = 4 * g + e;
           float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l4[e]));
-          if (diag) {
+          if (DIAG) {
             int q = qb0 + 8 * g + 4 * h + e;
             if (key > q) p = 0.f;
           }
@@ -161,6 +163,110 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
           bf16x8 a2 = lds_read_col8<D>(tQ, 32 * qb + 16 * cc, 32 * db, lane);
           dKt[db] = mfma32(a2, dsf[cc], dKt[db]);
         }
+      sched_reads_ahead_of_mfma<D / 8, 2, 4>();
+    };
+    // Both 32-query blocks of a tile that lies entirely below the diagonal for this wave, as one
+    // software-pipelined sequence of 4 x NS "slots" (one matrix instruction each).  The issue
+    // order is fixed by hand (scheduling fences between slots):
+    //   phase 1  S,dP of block 0
+    //   phase 2  S,dP of block 1        | vector work of block 0 (P, dS), one element per slot
+    //   phase 3  dV,dK += block 0       | vector work of block 1
+    //   phase 4  dV,dK += block 1
+    // and every LDS fragment read is issued AH slots before the matrix instruction that uses it.
+    auto tile_pipelined = [&]() {
+      constexpr int NS = D / 8;            // slots per phase
+      constexpr int AH = 4;                // LDS read-ahead, in slots
+      constexpr int R = 8;                 // fragment ring size (> AH)
+      constexpr int EPS = 16 / NS;         // score elements handled per slot
+      bf16x8 ring[R];
+      // slot s of an S/dP phase: kc = s/2, even -> S (Q_i, K_j), odd -> dP (dO_i, V_j)
+      auto rd_sdp = [&](int qb, int sl) -> bf16x8 {
+        return lds_read_row8<D>((sl & 1) ? tdO : tQ, 32 * qb + r, 16 * (sl >> 1) + 8 * h);
+      };
+      // slot s of a dV/dK phase: cc = s / (2 D/32), db = (s/2) % (D/32), even -> dV (dO_i^T), odd -> dK (Q_i^T)
+      auto rd_dvdk = [&](int qb, int sl) -> bf16x8 {
+        return lds_read_col8<D>((sl & 1) ? tQ : tdO, 32 * qb + 16 * (sl / (2 * (D / 32))),
+                                32 * ((sl >> 1) % (D / 32)), lane);
+      };
+      f32x16 s0, dp0, s1, dp1;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { s0[i] = 0.f; dp0[i] = 0.f; s1[i] = 0.f; dp1[i] = 0.f; }
+      bf16x8 pf0[2], dsf0[2], pf1[2], dsf1[2];
+      f32x4 lq0[4], dq0[4], lq1[4], dq1[4];       // L_i log2e and delta_i of the 16 rows a lane sees
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        lq0[g] = *reinterpret_cast<const f32x4*>(tL + 8 * g + 4 * h);
+        dq0[g] = *reinterpret_cast<const f32x4*>(tD + 8 * g + 4 * h);
+      }
+#pragma unroll
+      for (int a = 0; a < AH; ++a) ring[a] = rd_sdp(0, a);
+      __builtin_amdgcn_sched_barrier(0);
+      // ---- phase 1
+#pragma unroll
+      for (int sl = 0; sl < NS; ++sl) {
+        ring[(sl + AH) % R] = (sl + AH < NS) ? rd_sdp(0, sl + AH) : rd_sdp(1, sl + AH - NS);
+        if (sl & 1) dp0 = mfma32(ring[sl % R], vf[sl >> 1], dp0);
+        else s0 = mfma32(ring[sl % R], kf[sl >> 1], s0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        lq1[g] = *reinterpret_cast<const f32x4*>(tL + 32 + 8 * g + 4 * h);
+        dq1[g] = *reinterpret_cast<const f32x4*>(tD + 32 + 8 * g + 4 * h);
+      }
+      // ---- phase 2
+#pragma unroll
+      for (int sl = 0; sl < NS; ++sl) {
+        ring[(NS + sl + AH) % R] = (sl + AH < NS) ? rd_sdp(1, sl + AH) : rd_dvdk(0, sl + AH - NS);
+        if (sl & 1) dp1 = mfma32(ring[(NS + sl) % R], vf[sl >> 1], dp1);
+        else s1 = mfma32(ring[(NS + sl) % R], kf[sl >> 1], s1);
+#pragma unroll
+        for (int e = 0; e < EPS; ++e) {
+          const int i = sl * EPS + e;
+          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[i], c2, -lq0[i >> 2][i & 3]));
+          float ds = p * (dp0[i] - dq0[i >> 2][i & 3]);
+          pf0[i >> 3][i & 7] = (bf16_t)p;
+          dsf0[i >> 3][i & 7] = (bf16_t)ds;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // ---- phase 3
+#pragma unroll
+      for (int sl = 0; sl < NS; ++sl) {
+        ring[(2 * NS + sl + AH) % R] = (sl + AH < NS) ? rd_dvdk(0, sl + AH) : rd_dvdk(1, sl + AH - NS);
+        const int cc = sl / (2 * (D / 32)), db = (sl >> 1) % (D / 32);
+        if (sl & 1) dKt[db] = mfma32(ring[(2 * NS + sl) % R], dsf0[cc], dKt[db]);
+        else dVt[db] = mfma32(ring[(2 * NS + sl) % R], pf0[cc], dVt[db]);
+#pragma unroll
+        for (int e = 0; e < EPS; ++e) {
+          const int i = sl * EPS + e;
+          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[i], c2, -lq1[i >> 2][i & 3]));
+          float ds = p * (dp1[i] - dq1[i >> 2][i & 3]);
+          pf1[i >> 3][i & 7] = (bf16_t)p;
+          dsf1[i >> 3][i & 7] = (bf16_t)ds;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // ---- phase 4
+#pragma unroll
+      for (int sl = 0; sl < NS; ++sl) {
+        if (sl + AH < NS) ring[(3 * NS + sl + AH) % R] = rd_dvdk(1, sl + AH);
+        const int cc = sl / (2 * (D / 32)), db = (sl >> 1) % (D / 32);
+        if (sl & 1) dKt[db] = mfma32(ring[(3 * NS + sl) % R], dsf1[cc], dKt[db]);
+        else dVt[db] = mfma32(ring[(3 * NS + sl) % R], pf1[cc], dVt[db]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    if (!CAUSAL || qt0 >= kw + 31) {
+      tile_pipelined();
+    } else {
+#pragma unroll
+      for (int qb = 0; qb < kQTile / 32; ++qb) {
+        const int qb0 = qt0 + 32 * qb;
+        if (qb0 + 31 < kw) continue;               // every query of the block precedes every key of the wave
+        if (qb0 < kw + 31) qblock(std::true_type{}, qb);
+        else qblock(std::false_type{}, qb);
+      }
     }
     if (has_next) store_stats(buf ^ 1);
     wait_vmem();
@@ -171,7 +277,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
 }
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     bf16_t* __restrict__ dQ, int N, float alpha) {
@@ -229,10 +335,9 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     }
     const int kt0 = j * kKTile;
     if (!CAUSAL || (kt0 <= qw + 31)) {
-#pragma unroll
-      for (int kb = 0; kb < kKTile / 32; ++kb) {
+      auto kblock = [&](auto diag_c, int kb) {
+        constexpr bool DIAG = decltype(diag_c)::value;
         const int kb0 = kt0 + 32 * kb;
-        if (CAUSAL && (kb0 > qw + 31)) continue;   // every key of the block follows every query of the wave
         // ---- S^T = K_j Q_i^T, dP^T = V_j dO_i^T ; rows = keys, lane = query
         f32x16 s, dp;
 #pragma unroll
@@ -244,13 +349,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
           bf16x8 av = lds_read_row8<D>(tV, 32 * kb + r, 16 * kc + 8 * h);
           dp = mfma32(av, dof[kc], dp);
         }
+        sched_reads_ahead_of_mfma<D / 8, 1, 4>();
         bf16x8 dsf[2];
-        const bool diag = CAUSAL && (kb0 + 31 > qw);
         const int q = qw + r;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l2));
-          if (diag) {
+          if (DIAG) {
             int key = kb0 + 8 * (i >> 2) + 4 * h + (i & 3);
             if (key > q) p = 0.f;
           }
@@ -264,6 +369,14 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
             bf16x8 a = lds_read_col8<D>(tK, 32 * kb + 16 * cc, 32 * db, lane);
             dQt[db] = mfma32(a, dsf[cc], dQt[db]);
           }
+        sched_reads_ahead_of_mfma<D / 16, 2, 4>();
+      };
+#pragma unroll
+      for (int kb = 0; kb < kKTile / 32; ++kb) {
+        const int kb0 = kt0 + 32 * kb;
+        if (CAUSAL && (kb0 > qw + 31)) continue;   // every key of the block follows every query of the wave
+        if (CAUSAL && (kb0 + 31 > qw)) kblock(std::true_type{}, kb);
+        else kblock(std::false_type{}, kb);
       }
     }
     wait_vmem();

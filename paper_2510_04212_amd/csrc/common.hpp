@@ -104,20 +104,31 @@ DEVI float bf16_bits_to_float(unsigned short b) { return __uint_as_float(((unsig
 // 64/CH whole tile rows; the XOR swizzle is applied on the GLOBAL side: the lane that lands in
 // chunk slot s of row r fetches chunk s ^ swz(r) of that row.  256 threads (4 waves).
 // The caller must execute wait_vmem() and a barrier before any wave reads the tile.
+//
+// The instruction is emitted through inline assembly on purpose: when the compiler itself sees a
+// pending global->LDS transfer it turns every later LDS wait into "wait for everything"
+// (lgkmcnt(0)) and inserts a full vmcnt(0) before the first transposing LDS read, which defeats
+// both the fragment read-ahead and the overlap of the transfer with computation.  Hidden from
+// its bookkeeping, the transfer only makes the compiler's own vmcnt waits more conservative
+// (loads complete in order), and its completion is enforced explicitly by wait_vmem().
 template <int D> DEVI void tile_load_async(char* tile, const bf16_t* src_row0, int tid) {
   constexpr int CH = D / 8;                // 16-byte chunks per row
   constexpr int RPI = 64 / CH;             // rows per wave-instruction
   constexpr int NI = 64 / RPI / 4;         // instructions per wave
-  typedef __attribute__((address_space(3))) void lds_void;
-  typedef __attribute__((address_space(1))) const void glb_void;
+  typedef __attribute__((address_space(3))) char lds_char;
   const int wave = tid >> 6, lane = tid & 63;
+  const unsigned lds_tile = (unsigned)(unsigned long)((lds_char*)tile);
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
     const int rbase = (wave * NI + i) * RPI;
     const int row = rbase + lane / CH;
     const int c = (lane % CH) ^ swz<D>(row);
-    __builtin_amdgcn_global_load_lds((glb_void*)(src_row0 + (size_t)row * D + c * 8),
-                                     (lds_void*)(tile + rbase * (D * 2)), 16, 0, 0);
+    const bf16_t* g = src_row0 + (size_t)row * D + c * 8;
+    const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_tile + rbase * (D * 2));
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(m0v), "v"(g)
+                 : "m0");
   }
 }
 
@@ -131,6 +142,22 @@ DEVI float add_pair_bf16(bf16x2 p, float acc) {
   one[0] = (bf16_t)1.0f;
   one[1] = (bf16_t)1.0f;
   return __builtin_amdgcn_fdot2_f32_bf16(p, one, acc, false);
+}
+
+// Issue-order hints for one scheduling region (basic block) that holds N matrix instructions,
+// each fed by PER LDS fragment reads: the reads are issued AHEAD matrix instructions before
+// their use, so that LDS latency is covered by matrix-core work instead of stalling the wave.
+// (sched_group_barrier masks: 0x008 = MFMA, 0x100 = LDS read.)
+template <int N, int PER, int AHEAD> DEVI void sched_reads_ahead_of_mfma() {
+  static_assert(PER == 1 || PER == 2, "PER");
+  __builtin_amdgcn_sched_group_barrier(0x100, AHEAD * PER, 0);
+#pragma unroll
+  for (int i = 0; i < N - AHEAD; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, PER, 0);
+  }
+#pragma unroll
+  for (int i = 0; i < AHEAD; ++i) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
 }
 
 // Work-group index remap: consecutive hardware work-group ids go round-robin over the 8 XCDs

@@ -92,6 +92,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
           s[kb] = mfma32(a, qf[kc], s[kb]);
         }
       }
+      sched_reads_ahead_of_mfma<D / 8, 1, 4>();
       // ---- causal mask: key > query -> -inf (only tiles that cross the diagonal)
       if (CAUSAL && (k0 + kBc - 1 > qw)) {
         const int q = qw + r;
@@ -169,6 +170,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
             bf16x8 a = lds_read_col8<D>(tV, 32 * kb + 16 * cc, 32 * db, lane);
             acc[db] = mfma32(a, pf[kb][cc], acc[db]);
           }
+      sched_reads_ahead_of_mfma<D / 8, 2, 4>();
     }
     wait_vmem();
     __syncthreads();
