@@ -166,8 +166,9 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
       sched_reads_ahead_of_mfma<D / 8, 2, 4>();
     };
     // Both 32-query blocks of a tile that lies entirely below the diagonal for this wave, as one
-    // software-pipelined sequence of 4 x NS "slots" (one matrix instruction each).  The issue
-    // order is fixed by hand (scheduling fences between slots):
+    // software-pipelined sequence of 4 x NS "slots" (one matrix instruction each).  The phase
+    // order is fixed by hand (scheduling fences between the phases and between the slots of the
+    // two pure matrix phases; inside the mixed phases the compiler interleaves):
     //   phase 1  S,dP of block 0
     //   phase 2  S,dP of block 1        | vector work of block 0 (P, dS), one element per slot
     //   phase 3  dV,dK += block 0       | vector work of block 1
@@ -175,8 +176,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
     // and every LDS fragment read is issued AH slots before the matrix instruction that uses it.
     auto tile_pipelined = [&]() {
       constexpr int NS = D / 8;            // slots per phase
-      constexpr int AH = 4;                // LDS read-ahead, in slots
-      constexpr int R = 8;                 // fragment ring size (> AH)
+      constexpr int AH = (D >= 128) ? 8 : 4;  // LDS read-ahead, in slots
+      constexpr int R = 2 * AH;            // fragment ring size (> AH)
       constexpr int EPS = 16 / NS;         // score elements handled per slot
       bf16x8 ring[R];
       // slot s of an S/dP phase: kc = s/2, even -> S (Q_i, K_j), odd -> dP (dO_i, V_j)
@@ -228,8 +229,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
           pf0[i >> 3][i & 7] = (bf16_t)p;
           dsf0[i >> 3][i & 7] = (bf16_t)ds;
         }
-        __builtin_amdgcn_sched_barrier(0);
       }
+      __builtin_amdgcn_sched_barrier(0);
       // ---- phase 3
 #pragma unroll
       for (int sl = 0; sl < NS; ++sl) {
@@ -245,8 +246,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
           pf1[i >> 3][i & 7] = (bf16_t)p;
           dsf1[i >> 3][i & 7] = (bf16_t)ds;
         }
-        __builtin_amdgcn_sched_barrier(0);
       }
+      __builtin_amdgcn_sched_barrier(0);
       // ---- phase 4
 #pragma unroll
       for (int sl = 0; sl < NS; ++sl) {
