@@ -23,9 +23,15 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 matrix-core peak
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a copy
-# kernel of known size); filled in from the summaries under profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch (read + written) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
+# scaled by the same counter's reading for a 1 GiB device copy (see profiles/mid_hbm_traffic.txt).
+# Keyed by (workload, kernel); None = not measured.
+MEASURED_TRAFFIC_BYTES = {
+    ("mid", "fwd"): 542205443,
+    ("mid", "delta"): 270608090,
+    ("mid", "bwd_dkdv"): 810128010,
+    ("mid", "bwd_dq"): 689152677,
+}
 
 
 def main():
@@ -37,6 +43,9 @@ def main():
     ap.add_argument("--variant", default="mitigated", choices=["standard", "mitigated"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run plain device-to-device copies of 1 GiB (a kernel of known HBM traffic, "
+                         "used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (each GPU box has one); "
@@ -86,6 +95,14 @@ def main():
         per = {n: float(np.mean([evs[i][k].elapsed_time(evs[i][k + 1]) for i in range(steps)]))
                for k, n in enumerate(names)}
         return (t1 - t0) * 1e3 / steps, per
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     ms, per = timed(variant, args.steps, args.warmup)
     other = binding.STANDARD if variant == binding.MITIGATED else binding.MITIGATED
