@@ -93,9 +93,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
   // Q_i / dO_i tiles go global -> LDS asynchronously; L_i (pre-multiplied by log2 e) and delta_i
   // (64 floats each) pass through one register of threads 0..127.
   float sreg = 0.f;
+  TileLoader<D> loader;
+  loader.init(tid);
+  FragOffsets<D> fo;
+  init_frag_offsets<D>(fo, lane);
   auto load_tile = [&](int t, int buf) {
-    tile_load_async<D>(ldsQ + buf * TILE_BYTES, Qh + (size_t)t * kQTile * D, tid);
-    tile_load_async<D>(ldsdO + buf * TILE_BYTES, dOh + (size_t)t * kQTile * D, tid);
+    loader.load(ldsQ + buf * TILE_BYTES, Qh + (size_t)t * kQTile * D);
+    loader.load(ldsdO + buf * TILE_BYTES, dOh + (size_t)t * kQTile * D);
     if (tid < kQTile) sreg = Lh[t * kQTile + tid] * kLog2e;
     else if (tid < 2 * kQTile) sreg = Dh[t * kQTile + tid - kQTile];
   };
@@ -108,12 +112,14 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
   wait_vmem();
   __syncthreads();
 
-  for (int t = t0; t < nt; ++t) {
-    const int buf = (t - t0) & 1;
-    const char* tQ = ldsQ + buf * TILE_BYTES;
-    const char* tdO = ldsdO + buf * TILE_BYTES;
-    const float* tL = ldsL + buf * kQTile;
-    const float* tD = ldsD + buf * kQTile;
+  // One query tile; BUF (which LDS buffer holds it) is a compile-time constant so that every LDS
+  // address is a precomputed per-lane offset plus an immediate.
+  auto tile_step = [&](auto buf_c, int t) {
+    constexpr int buf = decltype(buf_c)::value;
+    const char* tQ = smem + buf * TILE_BYTES;
+    const char* tdO = smem + (2 + buf) * TILE_BYTES;
+    const float* tL = reinterpret_cast<const float*>(smem + 4 * TILE_BYTES) + buf * kQTile;
+    const float* tD = reinterpret_cast<const float*>(smem + 4 * TILE_BYTES) + 2 * kQTile + buf * kQTile;
     const bool has_next = (t + 1 < nt);
     if (has_next) load_tile(t + 1, buf ^ 1);
     const int qt0 = t * kQTile;
@@ -127,10 +133,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
       for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
 #pragma unroll
       for (int kc = 0; kc < D / 16; ++kc) {
-        bf16x8 aq = lds_read_row8<D>(tQ, 32 * qb + r, 16 * kc + 8 * h);
-        s = mfma32(aq, kf[kc], s);
-        bf16x8 ado = lds_read_row8<D>(tdO, 32 * qb + r, 16 * kc + 8 * h);
-        dp = mfma32(ado, vf[kc], dp);
+        s = mfma32(lds_row8<D>(tQ, fo, 32 * qb, kc), kf[kc], s);
+        dp = mfma32(lds_row8<D>(tdO, fo, 32 * qb, kc), vf[kc], dp);
       }
       sched_reads_ahead_of_mfma<D / 8, 1, 4>();
       // ---- P = exp(S - L) (step 9), dS = P o (dP - delta) (step 12)
@@ -158,10 +162,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
       for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
         for (int db = 0; db < D / 32; ++db) {
-          bf16x8 a1 = lds_read_col8<D>(tdO, 32 * qb + 16 * cc, 32 * db, lane);
-          dVt[db] = mfma32(a1, pf[cc], dVt[db]);
-          bf16x8 a2 = lds_read_col8<D>(tQ, 32 * qb + 16 * cc, 32 * db, lane);
-          dKt[db] = mfma32(a2, dsf[cc], dKt[db]);
+          dVt[db] = mfma32(lds_col8<D>(tdO, fo, 32 * qb + 16 * cc, db), pf[cc], dVt[db]);
+          dKt[db] = mfma32(lds_col8<D>(tQ, fo, 32 * qb + 16 * cc, db), dsf[cc], dKt[db]);
         }
       sched_reads_ahead_of_mfma<D / 8, 2, 4>();
     };
@@ -182,12 +184,12 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
       bf16x8 ring[R];
       // slot s of an S/dP phase: kc = s/2, even -> S (Q_i, K_j), odd -> dP (dO_i, V_j)
       auto rd_sdp = [&](int qb, int sl) -> bf16x8 {
-        return lds_read_row8<D>((sl & 1) ? tdO : tQ, 32 * qb + r, 16 * (sl >> 1) + 8 * h);
+        return lds_row8<D>((sl & 1) ? tdO : tQ, fo, 32 * qb, sl >> 1);
       };
       // slot s of a dV/dK phase: cc = s / (2 D/32), db = (s/2) % (D/32), even -> dV (dO_i^T), odd -> dK (Q_i^T)
       auto rd_dvdk = [&](int qb, int sl) -> bf16x8 {
-        return lds_read_col8<D>((sl & 1) ? tQ : tdO, 32 * qb + 16 * (sl / (2 * (D / 32))),
-                                32 * ((sl >> 1) % (D / 32)), lane);
+        return lds_col8<D>((sl & 1) ? tQ : tdO, fo, 32 * qb + 16 * (sl / (2 * (D / 32))),
+                           (sl >> 1) % (D / 32));
       };
       f32x16 s0, dp0, s1, dp1;
 #pragma unroll
@@ -272,6 +274,10 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
     if (has_next) store_stats(buf ^ 1);
     wait_vmem();
     __syncthreads();
+  };
+  for (int t = t0; t < nt; t += 2) {
+    tile_step(std::integral_constant<int, 0>{}, t);
+    if (t + 1 < nt) tile_step(std::integral_constant<int, 1>{}, t + 1);
   }
   store_acc_T<D>(dV + head_off + (size_t)(kw + r) * D, dVt, 1.0f, h);
   store_acc_T<D>(dK + head_off + (size_t)(kw + r) * D, dKt, alpha, h);
@@ -320,19 +326,21 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
   const int ntiles = CAUSAL ? (q0 + kQPerWG) / kKTile : N / kKTile;
   const float c2 = alpha * kLog2e;
 
-  tile_load_async<D>(ldsK, Kh, tid);
-  tile_load_async<D>(ldsV, Vh, tid);
+  TileLoader<D> loader;
+  loader.init(tid);
+  loader.load(ldsK, Kh);
+  loader.load(ldsV, Vh);
   wait_vmem();
   __syncthreads();
 
   for (int j = 0; j < ntiles; ++j) {
     const int buf = j & 1;
-    const char* tK = ldsK + buf * TILE_BYTES;
-    const char* tV = ldsV + buf * TILE_BYTES;
+    const char* tK = smem + buf * TILE_BYTES;
+    const char* tV = smem + (2 + buf) * TILE_BYTES;
     const bool has_next = (j + 1 < ntiles);
     if (has_next) {
-      tile_load_async<D>(ldsK + (buf ^ 1) * TILE_BYTES, Kh + (size_t)(j + 1) * kKTile * D, tid);
-      tile_load_async<D>(ldsV + (buf ^ 1) * TILE_BYTES, Vh + (size_t)(j + 1) * kKTile * D, tid);
+      loader.load(smem + (buf ^ 1) * TILE_BYTES, Kh + (size_t)(j + 1) * kKTile * D);
+      loader.load(smem + (2 + (buf ^ 1)) * TILE_BYTES, Vh + (size_t)(j + 1) * kKTile * D);
     }
     const int kt0 = j * kKTile;
     if (!CAUSAL || (kt0 <= qw + 31)) {
@@ -345,10 +353,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
         for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
 #pragma unroll
         for (int kc = 0; kc < D / 16; ++kc) {
-          bf16x8 ak = lds_read_row8<D>(tK, 32 * kb + r, 16 * kc + 8 * h);
-          s = mfma32(ak, qf[kc], s);
-          bf16x8 av = lds_read_row8<D>(tV, 32 * kb + r, 16 * kc + 8 * h);
-          dp = mfma32(av, dof[kc], dp);
+          s = mfma32(lds_read_row8<D>(tK, 32 * kb + r, 16 * kc + 8 * h), qf[kc], s);
+          dp = mfma32(lds_read_row8<D>(tV, 32 * kb + r, 16 * kc + 8 * h), dof[kc], dp);
         }
         sched_reads_ahead_of_mfma<D / 8, 1, 4>();
         bf16x8 dsf[2];
@@ -367,8 +373,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
         for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
           for (int db = 0; db < D / 32; ++db) {
-            bf16x8 a = lds_read_col8<D>(tK, 32 * kb + 16 * cc, 32 * db, lane);
-            dQt[db] = mfma32(a, dsf[cc], dQt[db]);
+            dQt[db] = mfma32(lds_read_col8<D>(tK, 32 * kb + 16 * cc, 32 * db, lane), dsf[cc], dQt[db]);
           }
         sched_reads_ahead_of_mfma<D / 16, 2, 4>();
       };

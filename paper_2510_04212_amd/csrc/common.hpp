@@ -78,6 +78,38 @@ template <int D> DEVI bf16x8 lds_read_col8(const char* tile, int row_base, int c
   return u.v;
 }
 
+// ---- The same two fragment reads with the lane-dependent part of the address precomputed.
+// The swizzle only looks at row bits 0..3, so moving a fragment by a multiple of 16 rows adds a
+// constant to the byte offset: per lane, D/16 offsets serve every row-major (natural) fragment
+// and 2 x D/32 offsets every column-major (transposing) one; the rest folds into the
+// instruction's immediate offset when the tile address is a compile-time constant.
+template <int D> struct FragOffsets {
+  int row[D / 16];          // natural read of columns 16kc + 8h .. +7 of row (lane & 31)
+  int col[2][D / 32];       // transposing reads: rows 4h + 8*half + 0..3, column 32db + (lane & 31)
+};
+template <int D> DEVI void init_frag_offsets(FragOffsets<D>& fo, int lane) {
+  const int r = lane & 31, h = lane >> 5, i = lane & 15;
+#pragma unroll
+  for (int kc = 0; kc < D / 16; ++kc) fo.row[kc] = tile_off<D>(r, 16 * kc + 8 * h);
+#pragma unroll
+  for (int half = 0; half < 2; ++half)
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+      fo.col[half][db] = tile_off<D>(4 * h + 8 * half + (i >> 2), 32 * db + (lane & 16) + ((i & 3) << 2));
+}
+// rows row_base + (lane & 31), row_base a multiple of 16
+template <int D> DEVI bf16x8 lds_row8(const char* tile, const FragOffsets<D>& fo, int row_base, int kc) {
+  return *reinterpret_cast<const bf16x8*>(tile + fo.row[kc] + row_base * (D * 2));
+}
+// k-slots = rows row_base + 8*(j/4) + 4h + (j%4), column 32db + (lane & 31); row_base a multiple of 16
+template <int D> DEVI bf16x8 lds_col8(const char* tile, const FragOffsets<D>& fo, int row_base, int db) {
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  union { struct { s16x4 lo, hi; } p; bf16x8 v; } u;
+  u.p.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + fo.col[0][db] + row_base * (D * 2)));
+  u.p.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + fo.col[1][db] + row_base * (D * 2)));
+  return u.v;
+}
+
 // Value held by the lane 32 positions away (lane ^ 32).
 DEVI float partner32(float x) {
   unsigned u = __float_as_uint(x);
@@ -111,26 +143,35 @@ DEVI float bf16_bits_to_float(unsigned short b) { return __uint_as_float(((unsig
 // both the fragment read-ahead and the overlap of the transfer with computation.  Hidden from
 // its bookkeeping, the transfer only makes the compiler's own vmcnt waits more conservative
 // (loads complete in order), and its completion is enforced explicitly by wait_vmem().
-template <int D> DEVI void tile_load_async(char* tile, const bf16_t* src_row0, int tid) {
-  constexpr int CH = D / 8;                // 16-byte chunks per row
-  constexpr int RPI = 64 / CH;             // rows per wave-instruction
-  constexpr int NI = 64 / RPI / 4;         // instructions per wave
-  typedef __attribute__((address_space(3))) char lds_char;
-  const int wave = tid >> 6, lane = tid & 63;
-  const unsigned lds_tile = (unsigned)(unsigned long)((lds_char*)tile);
+template <int D> struct TileLoader {
+  static constexpr int CH = D / 8;               // 16-byte chunks per row
+  static constexpr int RPI = 64 / CH;            // rows per wave-instruction
+  static constexpr int NI = 64 / RPI / 4;        // instructions per wave (4 waves share a tile)
+  unsigned voff[NI];                             // per-lane byte offset inside the source tile
+  unsigned lds_wave;                             // byte offset of this wave's first row in the LDS tile
+  DEVI void init(int tid) {
+    const int wave = tid >> 6, lane = tid & 63;
 #pragma unroll
-  for (int i = 0; i < NI; ++i) {
-    const int rbase = (wave * NI + i) * RPI;
-    const int row = rbase + lane / CH;
-    const int c = (lane % CH) ^ swz<D>(row);
-    const bf16_t* g = src_row0 + (size_t)row * D + c * 8;
-    const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_tile + rbase * (D * 2));
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :
-                 : "s"(m0v), "v"(g)
-                 : "m0");
+    for (int i = 0; i < NI; ++i) {
+      const int row = (wave * NI + i) * RPI + lane / CH;
+      const int c = (lane % CH) ^ swz<D>(row);
+      voff[i] = (unsigned)(row * D + c * 8) * 2u;
+    }
+    lds_wave = (unsigned)(wave * NI * RPI * D * 2);
   }
-}
+  // tile: LDS address of the destination tile; src: first row of the 64-row source tile (wave-uniform)
+  DEVI void load(const char* tile, const bf16_t* src) const {
+    typedef __attribute__((address_space(3))) const char lds_char;
+    const unsigned base = __builtin_amdgcn_readfirstlane((unsigned)(unsigned long)((lds_char*)tile) + lds_wave);
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :
+                   : "s"(base + (unsigned)(i * RPI * D * 2)), "v"(voff[i]), "s"(src)
+                   : "m0");
+    }
+  }
+};
 
 // s_waitcnt vmcnt(0): every outstanding global load (including loads into LDS) has landed.
 DEVI void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }

@@ -11,6 +11,8 @@
 // which keeps the per-query rescale factor uniform over a lane's accumulator registers.
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace {
 
 constexpr int kBr = 128;   // query rows per work-group
@@ -23,8 +25,6 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
   constexpr int TILE_BYTES = kBc * D * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   // layout: K buffers [2][TILE_BYTES], then V buffers [2][TILE_BYTES]
-  char* ldsK = smem;
-  char* ldsV = smem + 2 * TILE_BYTES;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -37,16 +37,26 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
   const int qt = nqt - 1 - (wg % nqt);          // heavy (late) query blocks first under the causal mask
   const int q0 = qt * kBr;
   const int qw = q0 + 32 * wave;                 // first query row of this wave
+  const int q = qw + r;
   const size_t head_off = (size_t)bh * N * D;
   const bf16_t* Qh = Q + head_off;
   const bf16_t* Kh = K + head_off;
   const bf16_t* Vh = V + head_off;
 
+  TileLoader<D> loader;
+  loader.init(tid);
+  FragOffsets<D> fo;
+  init_frag_offsets<D>(fo, lane);
+
+  const int ntiles = CAUSAL ? (q0 + kBr) / kBc : N / kBc;
+  loader.load(smem, Kh);
+  loader.load(smem + 2 * TILE_BYTES, Vh);
+
   // Q_i^T fragments: lane (r,h) holds Q[qw + r][16kc + 8h .. +7] for every kc.
   bf16x8 qf[D / 16];
 #pragma unroll
   for (int kc = 0; kc < D / 16; ++kc)
-    qf[kc] = *reinterpret_cast<const bf16x8*>(Qh + (size_t)(qw + r) * D + 16 * kc + 8 * h);
+    qf[kc] = *reinterpret_cast<const bf16x8*>(Qh + (size_t)q * D + 16 * kc + 8 * h);
 
   f32x16 acc[D / 32];
 #pragma unroll
@@ -56,28 +66,26 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
 
   float m = -INFINITY;      // running normaliser, natural-log units of the alpha-scaled scores
   float lsum = 0.f;         // this lane's share of the running row sum (its 32 of the 64 keys per tile)
-
-  const int ntiles = CAUSAL ? (q0 + kBr) / kBc : N / kBc;
   const float c2 = alpha * kLog2e;
+  // Alg. 3's test  r_m - alpha*s <= eps  in terms of the raw score s:  s >= (r_m - eps) / alpha
+  const float inv_alpha = 1.0f / alpha;
 
-  tile_load_async<D>(ldsK, Kh, tid);
-  tile_load_async<D>(ldsV, Vh, tid);
   wait_vmem();
   __syncthreads();
 
-  for (int j = 0; j < ntiles; ++j) {
-    const int buf = j & 1;
-    const char* tK = ldsK + buf * TILE_BYTES;
-    const char* tV = ldsV + buf * TILE_BYTES;
-    const bool has_next = (j + 1 < ntiles);
-    if (has_next) {   // lands in the other buffer while this tile is being processed
-      tile_load_async<D>(ldsK + (buf ^ 1) * TILE_BYTES, Kh + (size_t)(j + 1) * kBc * D, tid);
-      tile_load_async<D>(ldsV + (buf ^ 1) * TILE_BYTES, Vh + (size_t)(j + 1) * kBc * D, tid);
+  // One key tile; BUF (which LDS buffer holds it) is a compile-time constant so that every LDS
+  // address is a precomputed per-lane offset plus an immediate.
+  auto tile_step = [&](auto buf_c, int j) {
+    constexpr int BUF = decltype(buf_c)::value;
+    const char* tK = smem + BUF * TILE_BYTES;
+    const char* tV = smem + (2 + BUF) * TILE_BYTES;
+    if (j + 1 < ntiles) {   // lands in the other buffer while this tile is being processed
+      loader.load(smem + (BUF ^ 1) * TILE_BYTES, Kh + (size_t)(j + 1) * kBc * D);
+      loader.load(smem + (2 + (BUF ^ 1)) * TILE_BYTES, Vh + (size_t)(j + 1) * kBc * D);
     }
     const int k0 = j * kBc;
     // A wave whose 32 rows all lie above this key tile has nothing to do in it (causal).
-    const bool active = !CAUSAL || (k0 <= qw + 31);
-    if (active) {
+    if (!CAUSAL || (k0 <= qw + 31)) {
       // ---- S^T = K_j Q_i^T (Alg. 1 step 6); raw scores, alpha not yet applied
       f32x16 s[2];
 #pragma unroll
@@ -87,15 +95,11 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
 #pragma unroll
       for (int kc = 0; kc < D / 16; ++kc) {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          bf16x8 a = lds_read_row8<D>(tK, 32 * kb + r, 16 * kc + 8 * h);
-          s[kb] = mfma32(a, qf[kc], s[kb]);
-        }
+        for (int kb = 0; kb < 2; ++kb) s[kb] = mfma32(lds_row8<D>(tK, fo, 32 * kb, kc), qf[kc], s[kb]);
       }
       sched_reads_ahead_of_mfma<D / 8, 1, 4>();
-      // ---- causal mask: key > query -> -inf (only tiles that cross the diagonal)
+      // ---- causal mask: key > query -> -inf (only the tile that crosses the diagonal)
       if (CAUSAL && (k0 + kBc - 1 > qw)) {
-        const int q = qw + r;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -116,16 +120,14 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
       if (VARIANT == 1) {
         // Alg. 3: r_s = #{ r_m - S <= eps } over the tile row; a repeated maximum moves the
         // normaliser to beta*r_m (r_m > 0) or to 0 (r_m < 0).
-        float cnt = 0.f;
+        const float thr = (r_m - eps) * inv_alpha;
+        int cnt = 0;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            s[kb][i] *= alpha;                       // from here on s holds alpha-scaled scores
-            cnt += ((r_m - s[kb][i]) <= eps) ? 1.f : 0.f;
-          }
-        cnt = sum_with_partner32(cnt);
-        const bool repeated = cnt > 1.5f;
+          for (int i = 0; i < 16; ++i) cnt += (s[kb][i] >= thr) ? 1 : 0;
+        cnt += __shfl_xor(cnt, 32, 64);
+        const bool repeated = cnt > 1;
         m_prime = (repeated && r_m > 0.f) ? beta * r_m : r_m;
         m_prime = (repeated && r_m < 0.f) ? 0.f : m_prime;
       }
@@ -144,11 +146,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
           for (int jj = 0; jj < 8; jj += 2) {
             bf16x2 pp;
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-              float x = s[kb][8 * cc + jj + e];
-              float t = (VARIANT == 1) ? __builtin_fmaf(x, kLog2e, mneg) : __builtin_fmaf(x, c2, mneg);
-              pp[e] = (bf16_t)__builtin_amdgcn_exp2f(t);
-            }
+            for (int e = 0; e < 2; ++e)
+              pp[e] = (bf16_t)__builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][8 * cc + jj + e], c2, mneg));
             pf[kb][cc][jj] = pp[0];
             pf[kb][cc][jj + 1] = pp[1];
             psum = add_pair_bf16(pp, psum);
@@ -166,20 +165,22 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
 #pragma unroll
         for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
-          for (int db = 0; db < D / 32; ++db) {
-            bf16x8 a = lds_read_col8<D>(tV, 32 * kb + 16 * cc, 32 * db, lane);
-            acc[db] = mfma32(a, pf[kb][cc], acc[db]);
-          }
-      sched_reads_ahead_of_mfma<D / 8, 2, 4>();
+          for (int db = 0; db < D / 32; ++db)
+            acc[db] = mfma32(lds_col8<D>(tV, fo, 32 * kb + 16 * cc, db), pf[kb][cc], acc[db]);
     }
     wait_vmem();
     __syncthreads();
+  };
+
+  for (int j = 0; j < ntiles; j += 2) {
+    tile_step(std::integral_constant<int, 0>{}, j);
+    if (j + 1 < ntiles) tile_step(std::integral_constant<int, 1>{}, j + 1);
   }
 
   // ---- epilogue (Alg. 1 steps 10-13).  Rounding points of Sec. 3.3.2: the unnormalised
   // output is rounded to bf16 first, then divided by l, then rounded again.
   const float l = sum_with_partner32(lsum);
-  bf16_t* Oq = O + head_off + (size_t)(qw + r) * D;
+  bf16_t* Oq = O + head_off + (size_t)q * D;
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -192,7 +193,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
       }
       *reinterpret_cast<bf16x4*>(Oq + 32 * db + 8 * g + 4 * h) = o4;
     }
-  if (h == 0) LSE[(size_t)bh * N + qw + r] = m + __logf(l);
+  if (h == 0) LSE[(size_t)bh * N + q] = m + __logf(l);
 }
 
 }  // namespace
