@@ -90,8 +90,9 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
   const int nt = N / kQTile;
   const float c2 = alpha * kLog2e;
 
-  // Q_i / dO_i tiles go global -> LDS asynchronously; L_i (pre-multiplied by log2 e) and delta_i
-  // (64 floats each) pass through one register of threads 0..127.
+  // Q_i / dO_i tiles go global -> LDS asynchronously; L_i (pre-multiplied by log2 e) and -delta_i
+  // (64 floats each) pass through one register of threads 0..127.  The dP accumulator starts
+  // from -delta, so that the matrix instructions deliver dP - delta directly (Alg. 2 step 12).
   float sreg = 0.f;
   TileLoader<D> loader;
   loader.init(tid);
@@ -101,7 +102,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
     loader.load(ldsQ + buf * TILE_BYTES, Qh + (size_t)t * kQTile * D);
     loader.load(ldsdO + buf * TILE_BYTES, dOh + (size_t)t * kQTile * D);
     if (tid < kQTile) sreg = Lh[t * kQTile + tid] * kLog2e;
-    else if (tid < 2 * kQTile) sreg = Dh[t * kQTile + tid - kQTile];
+    else if (tid < 2 * kQTile) sreg = -Dh[t * kQTile + tid - kQTile];   // LDS holds -delta
   };
   auto store_stats = [&](int buf) {
     if (tid < kQTile) ldsL[buf * kQTile + tid] = sreg;
@@ -130,7 +131,11 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
       // ---- S = Q_i K_j^T and dP = dO_i V_j^T (Alg. 2 steps 8, 11); rows = queries, lane = key
       f32x16 s, dp;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+      for (int g = 0; g < 4; ++g) {
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(tD + 32 * qb + 8 * g + 4 * h);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { s[4 * g + e] = 0.f; dp[4 * g + e] = d4[e]; }
+      }
 #pragma unroll
       for (int kc = 0; kc < D / 16; ++kc) {
         s = mfma32(lds_row8<D>(tQ, fo, 32 * qb, kc), kf[kc], s);
@@ -143,7 +148,6 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const f32x4 l4 = *reinterpret_cast<const f32x4*>(tL + 32 * qb + 8 * g + 4 * h);
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(tD + 32 * qb + 8 * g + 4 * h);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int i = 4 * g + e;
@@ -152,7 +156,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
             int q = qb0 + 8 * g + 4 * h + e;
             if (key > q) p = 0.f;
           }
-          float ds = p * (dp[i] - d4[e]);
+          float ds = p * dp[i];                     // dp already holds dP - delta
           pf[i >> 3][i & 7] = (bf16_t)p;
           dsf[i >> 3][i & 7] = (bf16_t)ds;
         }
@@ -192,14 +196,18 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
                            (sl >> 1) % (D / 32));
       };
       f32x16 s0, dp0, s1, dp1;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) { s0[i] = 0.f; dp0[i] = 0.f; s1[i] = 0.f; dp1[i] = 0.f; }
       bf16x8 pf0[2], dsf0[2], pf1[2], dsf1[2];
-      f32x4 lq0[4], dq0[4], lq1[4], dq1[4];       // L_i log2e and delta_i of the 16 rows a lane sees
+      f32x4 lq0[4], lq1[4];                        // L_i log2e of the 16 rows a lane sees
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
+      for (int g = 0; g < 4; ++g) {                // the dP accumulators start from -delta_i
         lq0[g] = *reinterpret_cast<const f32x4*>(tL + 8 * g + 4 * h);
-        dq0[g] = *reinterpret_cast<const f32x4*>(tD + 8 * g + 4 * h);
+        const f32x4 d0 = *reinterpret_cast<const f32x4*>(tD + 8 * g + 4 * h);
+        const f32x4 d1 = *reinterpret_cast<const f32x4*>(tD + 32 + 8 * g + 4 * h);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          s0[4 * g + e] = 0.f; s1[4 * g + e] = 0.f;
+          dp0[4 * g + e] = d0[e]; dp1[4 * g + e] = d1[e];
+        }
       }
 #pragma unroll
       for (int a = 0; a < AH; ++a) ring[a] = rd_sdp(0, a);
@@ -213,10 +221,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        lq1[g] = *reinterpret_cast<const f32x4*>(tL + 32 + 8 * g + 4 * h);
-        dq1[g] = *reinterpret_cast<const f32x4*>(tD + 32 + 8 * g + 4 * h);
-      }
+      for (int g = 0; g < 4; ++g) lq1[g] = *reinterpret_cast<const f32x4*>(tL + 32 + 8 * g + 4 * h);
       // ---- phase 2
 #pragma unroll
       for (int sl = 0; sl < NS; ++sl) {
@@ -227,7 +232,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
         for (int e = 0; e < EPS; ++e) {
           const int i = sl * EPS + e;
           float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[i], c2, -lq0[i >> 2][i & 3]));
-          float ds = p * (dp0[i] - dq0[i >> 2][i & 3]);
+          float ds = p * dp0[i];
           pf0[i >> 3][i & 7] = (bf16_t)p;
           dsf0[i >> 3][i & 7] = (bf16_t)ds;
         }
@@ -244,7 +249,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
         for (int e = 0; e < EPS; ++e) {
           const int i = sl * EPS + e;
           float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[i], c2, -lq1[i >> 2][i & 3]));
-          float ds = p * (dp1[i] - dq1[i >> 2][i & 3]);
+          float ds = p * dp1[i];
           pf1[i >> 3][i & 7] = (bf16_t)p;
           dsf1[i >> 3][i & 7] = (bf16_t)ds;
         }
