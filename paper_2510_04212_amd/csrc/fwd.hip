@@ -120,14 +120,24 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
       if (VARIANT == 1) {
         // Alg. 3: r_s = #{ r_m - S <= eps } over the tile row; a repeated maximum moves the
         // normaliser to beta*r_m (r_m > 0) or to 0 (r_m < 0).
+        // The count only matters through "more than one".  Each comparison yields a 64-lane
+        // mask in scalar registers; "seen once" / "seen twice" masks are then maintained with
+        // scalar instructions (one vector instruction per element instead of three), and the two
+        // lanes that share a query row are merged at the end.
         const float thr = (r_m - eps) * inv_alpha;
-        int cnt = 0;
+        unsigned long long once = 0ull, twice = 0ull;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) cnt += (s[kb][i] >= thr) ? 1 : 0;
-        cnt += __shfl_xor(cnt, 32, 64);
-        const bool repeated = cnt > 1;
+          for (int i = 0; i < 16; ++i) {
+            const unsigned long long hit = __builtin_amdgcn_ballot_w64(s[kb][i] >= thr);
+            twice |= once & hit;
+            once |= hit;
+          }
+        const unsigned long long once_sw = (once >> 32) | (once << 32);
+        const unsigned long long twice_sw = (twice >> 32) | (twice << 32);
+        const unsigned long long rep = twice | twice_sw | (once & once_sw);
+        const bool repeated = ((rep >> lane) & 1ull) != 0ull;
         m_prime = (repeated && r_m > 0.f) ? beta * r_m : r_m;
         m_prime = (repeated && r_m < 0.f) ? 0.f : m_prime;
       }
