@@ -43,7 +43,7 @@ DEVI void store_acc_T(bf16_t* dst_row, const f32x16 (&acc)[D / 32], float scale,
     }
 }
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool RAGGED>
 __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
   const int wave = tid >> 6;
   const int r = lane & 31, h = lane >> 5;
 
-  const int nkt = N / kKeysPerWG;
+  const int nkt = (N + kKeysPerWG - 1) / kKeysPerWG;   // N need not be a multiple of the block
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nkt;
   const int kt = wg % nkt;                         // early key blocks see the most queries: heavy first
@@ -74,11 +74,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
   const float* Dh = delta + (size_t)bh * N;
 
   // K_j^T / V_j^T fragments (B operands): lane (r,h) holds K[kw + r][16kc + 8h .. +7]
+  // (keys past the sequence end read the last row; their gradients are not stored)
+  const int keyc = (RAGGED && kw + r >= N) ? N - 1 : kw + r;
   bf16x8 kf[D / 16], vf[D / 16];
 #pragma unroll
   for (int kc = 0; kc < D / 16; ++kc) {
-    kf[kc] = *reinterpret_cast<const bf16x8*>(K + head_off + (size_t)(kw + r) * D + 16 * kc + 8 * h);
-    vf[kc] = *reinterpret_cast<const bf16x8*>(V + head_off + (size_t)(kw + r) * D + 16 * kc + 8 * h);
+    kf[kc] = *reinterpret_cast<const bf16x8*>(K + head_off + (size_t)keyc * D + 16 * kc + 8 * h);
+    vf[kc] = *reinterpret_cast<const bf16x8*>(V + head_off + (size_t)keyc * D + 16 * kc + 8 * h);
   }
   f32x16 dVt[D / 32], dKt[D / 32];
 #pragma unroll
@@ -87,7 +89,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
     for (int i = 0; i < 16; ++i) { dVt[db][i] = 0.f; dKt[db][i] = 0.f; }
 
   const int t0 = CAUSAL ? k0 / kQTile : 0;         // first query tile that sees any key of this block
-  const int nt = N / kQTile;
+  const int nt = RAGGED ? (N + kQTile - 1) / kQTile : N / kQTile;
   const float c2 = alpha * kLog2e;
 
   // Q_i / dO_i tiles go global -> LDS asynchronously; L_i (pre-multiplied by log2 e) and -delta_i
@@ -99,10 +101,12 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
   FragOffsets<D> fo;
   init_frag_offsets<D>(fo, lane);
   auto load_tile = [&](int t, int buf) {
-    loader.load(ldsQ + buf * TILE_BYTES, Qh + (size_t)t * kQTile * D);
-    loader.load(ldsdO + buf * TILE_BYTES, dOh + (size_t)t * kQTile * D);
-    if (tid < kQTile) sreg = Lh[t * kQTile + tid] * kLog2e;
-    else if (tid < 2 * kQTile) sreg = -Dh[t * kQTile + tid - kQTile];   // LDS holds -delta
+    loader.template load_rows<RAGGED>(ldsQ + buf * TILE_BYTES, Qh, t * kQTile, N, tid);
+    loader.template load_rows<RAGGED>(ldsdO + buf * TILE_BYTES, dOh, t * kQTile, N, tid);
+    const int row = t * kQTile + (tid & (kQTile - 1));
+    const int rowc = (RAGGED && row >= N) ? N - 1 : row;
+    if (tid < kQTile) sreg = Lh[rowc] * kLog2e;
+    else if (tid < 2 * kQTile) sreg = -Dh[rowc];   // LDS holds -delta
   };
   auto store_stats = [&](int buf) {
     if (tid < kQTile) ldsL[buf * kQTile + tid] = sreg;
@@ -128,6 +132,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
     auto qblock = [&](auto diag_c, int qb) {
       constexpr bool DIAG = decltype(diag_c)::value;
       const int qb0 = qt0 + 32 * qb;
+      const bool tail = RAGGED && qb0 + 32 > N;              // some query rows lie past the sequence end
       // ---- S = Q_i K_j^T and dP = dO_i V_j^T (Alg. 2 steps 8, 11); rows = queries, lane = key
       f32x16 s, dp;
 #pragma unroll
@@ -142,6 +147,11 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
         dp = mfma32(lds_row8<D>(tdO, fo, 32 * qb, kc), vf[kc], dp);
       }
       sched_reads_ahead_of_mfma<D / 8, 1, 4>();
+      if (tail) {   // rows past the sequence end: P = exp(-inf) = 0, so they add nothing to dK, dV
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (qb0 + 8 * (i >> 2) + 4 * h + (i & 3) >= N) s[i] = -INFINITY;
+      }
       // ---- P = exp(S - L) (step 9), dS = P o (dP - delta) (step 12)
       bf16x8 pf[2], dsf[2];
       const int key = kw + r;
@@ -265,14 +275,15 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
         __builtin_amdgcn_sched_barrier(0);
       }
     };
-    if (!CAUSAL || qt0 >= kw + 31) {
+    if ((!CAUSAL || qt0 >= kw + 31) && (!RAGGED || qt0 + kQTile <= N)) {
       tile_pipelined();
     } else {
 #pragma unroll
       for (int qb = 0; qb < kQTile / 32; ++qb) {
         const int qb0 = qt0 + 32 * qb;
-        if (qb0 + 31 < kw) continue;               // every query of the block precedes every key of the wave
-        if (qb0 < kw + 31) qblock(std::true_type{}, qb);
+        if (CAUSAL && qb0 + 31 < kw) continue;     // every query of the block precedes every key of the wave
+        if (RAGGED && qb0 >= N) continue;                    // nothing but padding
+        if (CAUSAL && qb0 < kw + 31) qblock(std::true_type{}, qb);
         else qblock(std::false_type{}, qb);
       }
     }
@@ -284,11 +295,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
     tile_step(std::integral_constant<int, 0>{}, t);
     if (t + 1 < nt) tile_step(std::integral_constant<int, 1>{}, t + 1);
   }
-  store_acc_T<D>(dV + head_off + (size_t)(kw + r) * D, dVt, 1.0f, h);
-  store_acc_T<D>(dK + head_off + (size_t)(kw + r) * D, dKt, alpha, h);
+  if (!RAGGED || kw + r < N) {
+    store_acc_T<D>(dV + head_off + (size_t)(kw + r) * D, dVt, 1.0f, h);
+    store_acc_T<D>(dK + head_off + (size_t)(kw + r) * D, dKt, alpha, h);
+  }
 }
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool RAGGED>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
@@ -303,7 +316,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
   const int wave = tid >> 6;
   const int r = lane & 31, h = lane >> 5;
 
-  const int nqt = N / kQPerWG;
+  const int nqt = (N + kQPerWG - 1) / kQPerWG;
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nqt;
   const int qt = nqt - 1 - (wg % nqt);
@@ -314,27 +327,30 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
   const bf16_t* Vh = V + head_off;
 
   // Q_i^T / dO_i^T fragments (B operands): lane (r,h) holds Q[qw + r][16kc + 8h .. +7]
+  // (rows past the sequence end read the last row; their dQ is not stored)
+  const int qc = (RAGGED && qw + r >= N) ? N - 1 : qw + r;
   bf16x8 qf[D / 16], dof[D / 16];
 #pragma unroll
   for (int kc = 0; kc < D / 16; ++kc) {
-    qf[kc] = *reinterpret_cast<const bf16x8*>(Q + head_off + (size_t)(qw + r) * D + 16 * kc + 8 * h);
-    dof[kc] = *reinterpret_cast<const bf16x8*>(dO + head_off + (size_t)(qw + r) * D + 16 * kc + 8 * h);
+    qf[kc] = *reinterpret_cast<const bf16x8*>(Q + head_off + (size_t)qc * D + 16 * kc + 8 * h);
+    dof[kc] = *reinterpret_cast<const bf16x8*>(dO + head_off + (size_t)qc * D + 16 * kc + 8 * h);
   }
-  const float l2 = LSE[(size_t)bh * N + qw + r] * kLog2e;
-  const float dl = delta[(size_t)bh * N + qw + r];
+  const float l2 = LSE[(size_t)bh * N + qc] * kLog2e;
+  const float dl = delta[(size_t)bh * N + qc];
   f32x16 dQt[D / 32];
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
 #pragma unroll
     for (int i = 0; i < 16; ++i) dQt[db][i] = 0.f;
 
-  const int ntiles = CAUSAL ? (q0 + kQPerWG) / kKTile : N / kKTile;
+  const int kend = CAUSAL ? ((RAGGED && q0 + kQPerWG > N) ? N : q0 + kQPerWG) : N;
+  const int ntiles = RAGGED ? (kend + kKTile - 1) / kKTile : kend / kKTile;
   const float c2 = alpha * kLog2e;
 
   TileLoader<D> loader;
   loader.init(tid);
-  loader.load(ldsK, Kh);
-  loader.load(ldsV, Vh);
+  loader.template load_rows<RAGGED>(ldsK, Kh, 0, N, tid);
+  loader.template load_rows<RAGGED>(ldsV, Vh, 0, N, tid);
   wait_vmem();
   __syncthreads();
 
@@ -344,14 +360,15 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const char* tV = smem + (2 + buf) * TILE_BYTES;
     const bool has_next = (j + 1 < ntiles);
     if (has_next) {
-      loader.load(smem + (buf ^ 1) * TILE_BYTES, Kh + (size_t)(j + 1) * kKTile * D);
-      loader.load(smem + (2 + (buf ^ 1)) * TILE_BYTES, Vh + (size_t)(j + 1) * kKTile * D);
+      loader.template load_rows<RAGGED>(smem + (buf ^ 1) * TILE_BYTES, Kh, (j + 1) * kKTile, N, tid);
+      loader.template load_rows<RAGGED>(smem + (2 + (buf ^ 1)) * TILE_BYTES, Vh, (j + 1) * kKTile, N, tid);
     }
     const int kt0 = j * kKTile;
     if (!CAUSAL || (kt0 <= qw + 31)) {
       auto kblock = [&](auto diag_c, int kb) {
         constexpr bool DIAG = decltype(diag_c)::value;
         const int kb0 = kt0 + 32 * kb;
+        const bool tail = RAGGED && kb0 + 32 > N;            // some keys lie past the sequence end
         // ---- S^T = K_j Q_i^T, dP^T = V_j dO_i^T ; rows = keys, lane = query
         f32x16 s, dp;
 #pragma unroll
@@ -362,6 +379,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
           dp = mfma32(lds_read_row8<D>(tV, 32 * kb + r, 16 * kc + 8 * h), dof[kc], dp);
         }
         sched_reads_ahead_of_mfma<D / 8, 1, 4>();
+        if (tail) {   // keys past the sequence end: P = exp(-inf) = 0, so they add nothing to dQ
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            if (kb0 + 8 * (i >> 2) + 4 * h + (i & 3) >= N) s[i] = -INFINITY;
+        }
         bf16x8 dsf[2];
         const int q = qw + r;
 #pragma unroll
@@ -386,6 +408,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
       for (int kb = 0; kb < kKTile / 32; ++kb) {
         const int kb0 = kt0 + 32 * kb;
         if (CAUSAL && (kb0 > qw + 31)) continue;   // every key of the block follows every query of the wave
+        if (RAGGED && kb0 >= N) continue;                    // nothing but padding
         if (CAUSAL && (kb0 + 31 > qw)) kblock(std::true_type{}, kb);
         else kblock(std::false_type{}, kb);
       }
@@ -393,7 +416,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     wait_vmem();
     __syncthreads();
   }
-  store_acc_T<D>(dQ + head_off + (size_t)(qw + r) * D, dQt, alpha, h);
+  if (!RAGGED || qw + r < N) store_acc_T<D>(dQ + head_off + (size_t)(qw + r) * D, dQt, alpha, h);
 }
 
 template <typename KernT>
@@ -405,31 +428,31 @@ static hipError_t set_smem(KernT kern, int smem, bool& done) {
   return e;
 }
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool RAGGED>
 static hipError_t launch_dkdv(const void* Q, const void* K, const void* V, const void* dO,
                               const float* LSE, const float* delta, void* dK, void* dV, int BH,
                               int N, float alpha, hipStream_t st) {
   constexpr int smem = 4 * kQTile * D * 2 + 4 * kQTile * (int)sizeof(float);
   static bool set = false;
-  auto k = attn_bwd_dkdv_kernel<D, CAUSAL>;
+  auto k = attn_bwd_dkdv_kernel<D, CAUSAL, RAGGED>;
   hipError_t e;
   if ((e = set_smem(k, smem, set)) != hipSuccess) return e;
-  hipLaunchKernelGGL(k, dim3(BH * (N / kKeysPerWG)), dim3(256), smem, st, (const bf16_t*)Q,
+  hipLaunchKernelGGL(k, dim3(BH * ((N + kKeysPerWG - 1) / kKeysPerWG)), dim3(256), smem, st, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
                      (bf16_t*)dK, (bf16_t*)dV, N, alpha);
   return hipGetLastError();
 }
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool RAGGED>
 static hipError_t launch_dq(const void* Q, const void* K, const void* V, const void* dO,
                             const float* LSE, const float* delta, void* dQ, int BH, int N,
                             float alpha, hipStream_t st) {
   constexpr int smem = 4 * kKTile * D * 2;
   static bool set = false;
-  auto k = attn_bwd_dq_kernel<D, CAUSAL>;
+  auto k = attn_bwd_dq_kernel<D, CAUSAL, RAGGED>;
   hipError_t e;
   if ((e = set_smem(k, smem, set)) != hipSuccess) return e;
-  hipLaunchKernelGGL(k, dim3(BH * (N / kQPerWG)), dim3(256), smem, st, (const bf16_t*)Q,
+  hipLaunchKernelGGL(k, dim3(BH * ((N + kQPerWG - 1) / kQPerWG)), dim3(256), smem, st, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
                      (bf16_t*)dQ, N, alpha);
   return hipGetLastError();
@@ -440,19 +463,25 @@ static hipError_t launch_dq(const void* Q, const void* K, const void* V, const v
 hipError_t attn_bwd_dkdv_dispatch(const void* Q, const void* K, const void* V, const void* dO,
                                   const float* LSE, const float* delta, void* dK, void* dV,
                                   int BH, int N, int d, int causal, float alpha, hipStream_t st) {
-  if (d == 64) return causal ? launch_dkdv<64, true>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, st)
-                             : launch_dkdv<64, false>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, st);
-  if (d == 128) return causal ? launch_dkdv<128, true>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, st)
-                              : launch_dkdv<128, false>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, st);
+  const bool ragged = (N % kKeysPerWG) != 0;     // the aligned kernels carry no bounds handling
+#define CASE(DD, CC, RR)                                                \
+  if (d == DD && (causal != 0) == CC && ragged == RR)                   \
+    return launch_dkdv<DD, CC, RR>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, st);
+  CASE(64, false, false) CASE(64, false, true) CASE(64, true, false) CASE(64, true, true)
+  CASE(128, false, false) CASE(128, false, true) CASE(128, true, false) CASE(128, true, true)
+#undef CASE
   return hipErrorInvalidValue;
 }
 
 hipError_t attn_bwd_dq_dispatch(const void* Q, const void* K, const void* V, const void* dO,
                                 const float* LSE, const float* delta, void* dQ, int BH, int N,
                                 int d, int causal, float alpha, hipStream_t st) {
-  if (d == 64) return causal ? launch_dq<64, true>(Q, K, V, dO, LSE, delta, dQ, BH, N, alpha, st)
-                             : launch_dq<64, false>(Q, K, V, dO, LSE, delta, dQ, BH, N, alpha, st);
-  if (d == 128) return causal ? launch_dq<128, true>(Q, K, V, dO, LSE, delta, dQ, BH, N, alpha, st)
-                              : launch_dq<128, false>(Q, K, V, dO, LSE, delta, dQ, BH, N, alpha, st);
+  const bool ragged = (N % kQPerWG) != 0;
+#define CASE(DD, CC, RR)                                                \
+  if (d == DD && (causal != 0) == CC && ragged == RR)                   \
+    return launch_dq<DD, CC, RR>(Q, K, V, dO, LSE, delta, dQ, BH, N, alpha, st);
+  CASE(64, false, false) CASE(64, false, true) CASE(64, true, false) CASE(64, true, true)
+  CASE(128, false, false) CASE(128, false, true) CASE(128, true, false) CASE(128, true, true)
+#undef CASE
   return hipErrorInvalidValue;
 }

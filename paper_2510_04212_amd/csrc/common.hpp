@@ -159,6 +159,33 @@ template <int D> struct TileLoader {
     }
     lds_wave = (unsigned)(wave * NI * RPI * D * 2);
   }
+  // Same for a source tile of which only the first `valid` rows (1..64) exist: rows beyond them
+  // re-read the last valid row, so that nothing is fetched out of bounds and the LDS tile holds
+  // finite values everywhere (the kernels mask those rows / columns out).
+  DEVI void load_clamped(const char* tile, const bf16_t* src, int valid, int tid) const {
+    typedef __attribute__((address_space(3))) const char lds_char;
+    const int wave = tid >> 6, lane = tid & 63;
+    const unsigned base = __builtin_amdgcn_readfirstlane((unsigned)(unsigned long)((lds_char*)tile) + lds_wave);
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int row = (wave * NI + i) * RPI + lane / CH;
+      const int c = (lane % CH) ^ swz<D>(row);
+      const int rc = row < valid ? row : valid - 1;
+      const unsigned vo = (unsigned)(rc * D + c * 8) * 2u;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :
+                   : "s"(base + (unsigned)(i * RPI * D * 2)), "v"(vo), "s"(src)
+                   : "m0");
+    }
+  }
+  // Tile starting at row `row0` of a tensor with `N` rows (row0 < N).  RAGGED: the tile may
+  // reach past row N-1 and is then loaded clamped; otherwise every tile is known to be full.
+  template <bool RAGGED>
+  DEVI void load_rows(const char* tile, const bf16_t* tensor, int row0, int N, int tid) const {
+    const bf16_t* src = tensor + (size_t)row0 * D;
+    if (!RAGGED || row0 + 64 <= N) load(tile, src);
+    else load_clamped(tile, src, N - row0, tid);
+  }
   // tile: LDS address of the destination tile; src: first row of the 64-row source tile (wave-uniform)
   DEVI void load(const char* tile, const bf16_t* src) const {
     typedef __attribute__((address_space(3))) const char lds_char;

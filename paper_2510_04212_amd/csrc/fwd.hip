@@ -18,7 +18,7 @@ namespace {
 constexpr int kBr = 128;   // query rows per work-group
 constexpr int kBc = 64;    // key rows per tile
 
-template <int D, bool CAUSAL, int VARIANT>
+template <int D, bool CAUSAL, int VARIANT, bool RAGGED>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, float* __restrict__ LSE, int N, float alpha, float beta, float eps) {
@@ -31,13 +31,16 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
   const int wave = tid >> 6;
   const int r = lane & 31, h = lane >> 5;
 
-  const int nqt = N / kBr;
+  // RAGGED: N is not a multiple of the block; the last block's missing rows are computed on
+  // clamped data and not stored, and keys past the end are masked like future keys.
+  const int nqt = (N + kBr - 1) / kBr;
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nqt;
   const int qt = nqt - 1 - (wg % nqt);          // heavy (late) query blocks first under the causal mask
   const int q0 = qt * kBr;
   const int qw = q0 + 32 * wave;                 // first query row of this wave
   const int q = qw + r;
+  const int qc = (RAGGED && q >= N) ? N - 1 : q;   // row actually read for this lane
   const size_t head_off = (size_t)bh * N * D;
   const bf16_t* Qh = Q + head_off;
   const bf16_t* Kh = K + head_off;
@@ -48,15 +51,16 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
   FragOffsets<D> fo;
   init_frag_offsets<D>(fo, lane);
 
-  const int ntiles = CAUSAL ? (q0 + kBr) / kBc : N / kBc;
-  loader.load(smem, Kh);
-  loader.load(smem + 2 * TILE_BYTES, Vh);
+  const int kend = CAUSAL ? ((RAGGED && q0 + kBr > N) ? N : q0 + kBr) : N;   // keys [0, kend) can matter to this block
+  const int ntiles = RAGGED ? (kend + kBc - 1) / kBc : kend / kBc;
+  loader.template load_rows<RAGGED>(smem, Kh, 0, N, tid);
+  loader.template load_rows<RAGGED>(smem + 2 * TILE_BYTES, Vh, 0, N, tid);
 
   // Q_i^T fragments: lane (r,h) holds Q[qw + r][16kc + 8h .. +7] for every kc.
   bf16x8 qf[D / 16];
 #pragma unroll
   for (int kc = 0; kc < D / 16; ++kc)
-    qf[kc] = *reinterpret_cast<const bf16x8*>(Qh + (size_t)q * D + 16 * kc + 8 * h);
+    qf[kc] = *reinterpret_cast<const bf16x8*>(Qh + (size_t)qc * D + 16 * kc + 8 * h);
 
   f32x16 acc[D / 32];
 #pragma unroll
@@ -80,8 +84,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
     const char* tK = smem + BUF * TILE_BYTES;
     const char* tV = smem + (2 + BUF) * TILE_BYTES;
     if (j + 1 < ntiles) {   // lands in the other buffer while this tile is being processed
-      loader.load(smem + (BUF ^ 1) * TILE_BYTES, Kh + (size_t)(j + 1) * kBc * D);
-      loader.load(smem + (2 + (BUF ^ 1)) * TILE_BYTES, Vh + (size_t)(j + 1) * kBc * D);
+      loader.template load_rows<RAGGED>(smem + (BUF ^ 1) * TILE_BYTES, Kh, (j + 1) * kBc, N, tid);
+      loader.template load_rows<RAGGED>(smem + (2 + (BUF ^ 1)) * TILE_BYTES, Vh, (j + 1) * kBc, N, tid);
     }
     const int k0 = j * kBc;
     // A wave whose 32 rows all lie above this key tile has nothing to do in it (causal).
@@ -98,14 +102,15 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
         for (int kb = 0; kb < 2; ++kb) s[kb] = mfma32(lds_row8<D>(tK, fo, 32 * kb, kc), qf[kc], s[kb]);
       }
       sched_reads_ahead_of_mfma<D / 8, 1, 4>();
-      // ---- causal mask: key > query -> -inf (only the tile that crosses the diagonal)
-      if (CAUSAL && (k0 + kBc - 1 > qw)) {
+      // ---- mask: causal (key > query) in the tile that crosses the diagonal, and keys beyond
+      // the sequence end in the last, partial tile -> -inf
+      if ((CAUSAL && (k0 + kBc - 1 > qw)) || (RAGGED && k0 + kBc > N)) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             int key = k0 + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
-            if (key > q) s[kb][i] = -INFINITY;
+            if ((CAUSAL && key > q) || (RAGGED && key >= N)) s[kb][i] = -INFINITY;
           }
       }
       // ---- tile row maximum r_m (of the alpha-scaled scores)
@@ -190,6 +195,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
   // ---- epilogue (Alg. 1 steps 10-13).  Rounding points of Sec. 3.3.2: the unnormalised
   // output is rounded to bf16 first, then divided by l, then rounded again.
   const float l = sum_with_partner32(lsum);
+  if (RAGGED && q >= N) return;                            // rows past the sequence end exist only as padding
   bf16_t* Oq = O + head_off + (size_t)q * D;
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
@@ -210,19 +216,19 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
 
 extern "C" int attn_fwd_key_tile(int d) { return (d == 64 || d == 128) ? kBc : 0; }
 
-template <int D, bool CAUSAL, int VARIANT>
+template <int D, bool CAUSAL, int VARIANT, bool RAGGED>
 static hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
                              int BH, int N, float alpha, float beta, float eps, hipStream_t st) {
   constexpr int smem = 4 * kBc * D * 2;
   static bool attr_set = false;
-  auto kern = attn_fwd_kernel<D, CAUSAL, VARIANT>;
+  auto kern = attn_fwd_kernel<D, CAUSAL, VARIANT, RAGGED>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  dim3 grid(BH * (N / kBr));
+  dim3 grid(BH * ((N + kBr - 1) / kBr));
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, (const bf16_t*)Q, (const bf16_t*)K,
                      (const bf16_t*)V, (bf16_t*)O, LSE, N, alpha, beta, eps);
   return hipGetLastError();
@@ -234,7 +240,8 @@ hipError_t attn_fwd_dispatch(const void* Q, const void* K, const void* V, void* 
                              float beta, float eps, hipStream_t st) {
 #define CASE(DD, CC, VV)                                                                     \
   if (d == DD && (causal != 0) == CC && variant == VV)                                        \
-    return launch_fwd<DD, CC, VV>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, st);
+    return (N % kBr) ? launch_fwd<DD, CC, VV, true>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, st) \
+                     : launch_fwd<DD, CC, VV, false>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, st);
   CASE(64, false, 0) CASE(64, false, 1) CASE(64, true, 0) CASE(64, true, 1)
   CASE(128, false, 0) CASE(128, false, 1) CASE(128, true, 0) CASE(128, true, 1)
 #undef CASE

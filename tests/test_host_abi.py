@@ -42,7 +42,8 @@ def test_key_tile_and_workspace_queries(binding):
     assert binding.fwd_key_tile(96) == 0
     assert binding.bwd_workspace_bytes(4, 32, 4096, 128) == 4 * 32 * 4096 * 4
     assert binding.bwd_workspace_bytes(1, 1, 128, 64) == 512          # rounded up to 256
-    assert binding.bwd_workspace_bytes(1, 1, 100, 64) == 0            # unsupported shape
+    assert binding.bwd_workspace_bytes(1, 1, 100, 64) == 512          # any N >= 1 is accepted
+    assert binding.bwd_workspace_bytes(1, 1, 128, 96) == 0            # unsupported head dim
     assert binding.bwd_workspace_bytes(0, 4, 128, 64) == 0
 
 
@@ -53,7 +54,6 @@ def test_argument_validation_happens_on_the_host(binding):
     p = ctypes.c_void_p(0x1000)          # a non-NULL, aligned fake pointer: never dereferenced
     mis = ctypes.c_void_p(0x1004)
     fwd = lambda Q, K, V, O, L, B, H, N, d, var=0, scale=0.125: lib.attn_fwd(Q, K, V, O, L, B, H, N, d, 1, scale, var, None)
-    assert fwd(p, p, p, p, p, 1, 1, 100, 64) == UNSUP        # N not a multiple of 128
     assert fwd(p, p, p, p, p, 1, 1, 128, 96) == UNSUP        # head dim
     assert fwd(p, p, p, p, p, 1, 1, 0, 64) == UNSUP
     assert fwd(p, p, p, p, p, -1, 1, 128, 64) == BAD
@@ -68,7 +68,7 @@ def test_argument_validation_happens_on_the_host(binding):
     ex = lambda beta, eps: lib.attn_fwd_ex(q, p, p, p, p, 1, 1, 128, 64, 1, 0.125, 1, beta, eps, None)
     assert ex(1.0, 1e-3) == BAD and ex(2.0, -1.0) == BAD and ex(float("nan"), 1e-3) == BAD
     assert lib.attn_delta(None, p, p, 1, 1, 128, 64, None) == NULL
-    assert lib.attn_delta(p, p, p, 1, 1, 130, 64, None) == UNSUP
+    assert lib.attn_delta(p, p, p, 1, 1, 130, 32, None) == UNSUP
     assert lib.attn_delta(None, None, None, 2, 0, 128, 64, None) == OK
     ptrs = [ctypes.c_void_p(0x1000 * (i + 1)) for i in range(9)]
     ws = ctypes.c_void_p(0x100000)
@@ -76,7 +76,8 @@ def test_argument_validation_happens_on_the_host(binding):
     assert bwd(ptrs, ws, 0) == WS                            # too small
     assert bwd(ptrs, ctypes.c_void_p(0x100010), 4096) == WS  # not 256-byte aligned
     assert bwd(ptrs, None, 4096) == NULL
-    assert bwd(ptrs, ws, 4096, N=64) == UNSUP
+    assert bwd(ptrs, ws, 4096, N=0) == UNSUP
+    assert bwd(ptrs, ws, 256, N=100) == WS                   # ragged N is accepted; 100 floats need 512 bytes
     alias = list(ptrs); alias[6] = alias[0]
     assert bwd(alias, ws, 4096) == BAD                       # dQ aliases Q
     alias = list(ptrs); alias[7] = alias[8]
