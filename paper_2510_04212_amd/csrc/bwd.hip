@@ -337,6 +337,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
   }
   const float l2 = LSE[(size_t)bh * N + qc] * kLog2e;
   const float dl = delta[(size_t)bh * N + qc];
+  // -delta_i in all 16 accumulator slots of the lane: the third operand of the first dP^T matrix
+  // instruction of every key block, which then delivers dP - delta with no vector instruction
+  // (Alg. 2 step 12).  Kept opaque so that it stays resident instead of being rebuilt per block.
+  f32x16 neg_delta;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) neg_delta[i] = -dl;
+  asm volatile("" : "+v"(neg_delta));
   f32x16 dQt[D / 32];
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
@@ -372,11 +379,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
         // ---- S^T = K_j Q_i^T, dP^T = V_j dO_i^T ; rows = keys, lane = query
         f32x16 s, dp;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+        for (int i = 0; i < 16; ++i) s[i] = 0.f;
 #pragma unroll
         for (int kc = 0; kc < D / 16; ++kc) {
           s = mfma32(lds_read_row8<D>(tK, 32 * kb + r, 16 * kc + 8 * h), qf[kc], s);
-          dp = mfma32(lds_read_row8<D>(tV, 32 * kb + r, 16 * kc + 8 * h), dof[kc], dp);
+          dp = mfma32(lds_read_row8<D>(tV, 32 * kb + r, 16 * kc + 8 * h), dof[kc], kc == 0 ? neg_delta : dp);
         }
         sched_reads_ahead_of_mfma<D / 8, 1, 4>();
         if (tail) {   // keys past the sequence end: P = exp(-inf) = 0, so they add nothing to dQ
@@ -393,7 +400,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
             int key = kb0 + 8 * (i >> 2) + 4 * h + (i & 3);
             if (key > q) p = 0.f;
           }
-          dsf[i >> 3][i & 7] = (bf16_t)(p * (dp[i] - dl));
+          dsf[i >> 3][i & 7] = (bf16_t)(p * dp[i]);      // dp already holds dP - delta
         }
         // ---- dQ_i^T += K_j^T dS^T (step 13)
 #pragma unroll
