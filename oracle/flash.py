@@ -68,11 +68,18 @@ def _tile_scores(Qw, Kj, alpha, causal, k0, prec):
     return S.astype(prec.dtype)
 
 
-def forward(Q, K, V, alpha, causal, variant=STANDARD, beta=2.0, eps=1e-3, Bc=None, prec=BF16):
+def forward(Q, K, V, alpha, causal, variant=STANDARD, beta=2.0, eps=1e-3, Bc=None, prec=BF16,
+            round_obar=True):
     """One head, Alg. 1 (variant 0) or Alg. 3 (variant 1).
+
+    round_obar=False drops rounding point (r3): the unnormalised output stays in working
+    precision until after the division (the experiment of Sec. 3.3.2 in which computing only
+    O-bar = P-bar V in FP32 is enough to stabilise training); (r4) is kept.
 
     Returns a dict:
       O      [N,d]  output (bf16-valued in BF16 mode)
+      Ohp    [N,d]  Oacc / l with no rounding at (r3) or (r4): the "O computed in high
+                    precision" of Sec. 3.2, from which delta_hp = rowsum(dO o Ohp) is formed
       L      [N]    logsumexp  m + log l            (Alg. 1 step 12)
       Obar   [N,d]  unnormalised output after rounding point (r3)
       Oacc   [N,d]  unnormalised output before (r3) (working precision)
@@ -114,17 +121,22 @@ def forward(Q, K, V, alpha, causal, variant=STANDARD, beta=2.0, eps=1e-3, Bc=Non
             acc = (corr[:, None] * acc + Phat @ Vj).astype(dt)            # step 8
             ones += np.sum(Phat == dt(1.0), axis=1)
             m = m_new
-        Obar = prec.rnd(acc).astype(dt)                                    # (r3)
+        Obar = prec.rnd(acc).astype(dt) if round_obar else acc            # (r3)
         O = prec.rnd(Obar / ell[:, None]).astype(dt)                       # step 10, (r4)
+        Ohp = (acc / ell[:, None]).astype(dt)
         L = (m + np.log(ell)).astype(dt)                                   # step 11
     return {"O": O, "L": L, "Obar": Obar, "Oacc": acc, "ell": ell, "m": m,
-            "fired": fired, "ones": ones}
+            "fired": fired, "ones": ones, "Ohp": Ohp}
 
 
 def backward(Q, K, V, O, dO, L, alpha, causal, Bc=None, Br=None, prec=BF16):
     """One head, Alg. 2.  O and L are the forward pass's outputs (O bf16-valued in BF16 mode).
 
-    Returns dQ, dK, dV (bf16-valued in BF16 mode) and delta = rowsum(dO o O) in working precision.
+    O is used for delta = rowsum(dO o O) only (step 4) and is taken as given: passing the
+    forward pass's `Ohp` instead of its bf16 `O` gives delta_hp, the variant of Sec. 3.2 that
+    restores stability with everything else unchanged.
+
+    Returns dQ, dK, dV (bf16-valued in BF16 mode) and delta in working precision.
     """
     dt = prec.dtype
     Qw = np.asarray(Q, dtype=dt); Kw = np.asarray(K, dtype=dt); Vw = np.asarray(V, dtype=dt)

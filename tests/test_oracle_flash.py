@@ -163,6 +163,44 @@ def test_bias_sign_and_its_removal_on_one_signed_values():
     assert d[0] > 0 and abs(d[1]) < abs(d[0]) / 10
 
 
+def test_high_precision_output_variants_of_sec_3_2():
+    """Sec. 3.2 / 3.3.2: with the STANDARD forward on one-signed values,
+      * delta_hp = rowsum(dO o O_hp), O_hp being the output with no bf16 rounding, has no bias
+        (its error against the fp64 delta is float32-level plus the bf16 rounding of P-bar,
+        zero-mean), while delta_lp - delta_hp is positive;
+      * dropping only the rounding of the unnormalised output ("computing only O-bar = P-bar V in
+        FP32 is sufficient") removes the bias of O as well;
+      * the gradients computed from delta_hp differ from those computed from delta_lp by
+        alpha diag(delta_lp - delta_hp) P K up to rounding (Eq. for dQ_hp - dQ_lp, Sec. 3.3.1)."""
+    w = synth.WORKLOADS["pairs_skew"]
+    e_lp, e_single, d_lp, d_hp = [], [], [], []
+    for h in range(3):
+        x = synth.head_f64(w, 0, h)
+        O, L = exact.forward(x["Q"], x["K"], x["V"], w.alpha, True)
+        d_exact = np.sum(x["dO"] * O, axis=1)
+        f = flash.forward(x["Q"], x["K"], x["V"], w.alpha, True, 0, Bc=64)
+        g = flash.forward(x["Q"], x["K"], x["V"], w.alpha, True, 0, Bc=64, round_obar=False)
+        assert np.array_equal(f["Ohp"], g["Ohp"]) and np.array_equal(f["L"], g["L"])
+        assert np.array_equal(g["Obar"], g["Oacc"])            # nothing rounded before the division
+        e_lp.append((f["O"] - O).ravel()); e_single.append((g["O"] - O).ravel())
+        d_lp.append(np.sum(x["dO"] * f["O"], axis=1) - d_exact)
+        d_hp.append(np.sum(x["dO"] * f["Ohp"].astype(np.float64), axis=1) - d_exact)
+    e_lp, e_single = np.concatenate(e_lp), np.concatenate(e_single)
+    d_lp, d_hp = np.concatenate(d_lp), np.concatenate(d_hp)
+    assert e_lp.mean() < 0 and abs(e_single.mean()) < abs(e_lp.mean()) / 10
+    assert d_lp.mean() > 0 and abs(d_hp.mean()) < d_lp.mean() / 10
+    assert np.mean(d_lp - d_hp) > 0
+    # gradient difference, one head, fp64 working precision so that only delta differs
+    x = synth.head_f64(w, 0, 0)
+    f = flash.forward(x["Q"], x["K"], x["V"], w.alpha, True, 0, Bc=64)
+    lp = flash.backward(x["Q"], x["K"], x["V"], f["O"], x["dO"], f["L"], w.alpha, True, Bc=64, prec=flash.FP64)
+    hp = flash.backward(x["Q"], x["K"], x["V"], f["Ohp"], x["dO"], f["L"], w.alpha, True, Bc=64, prec=flash.FP64)
+    P = np.exp(exact.scores(x["Q"], x["K"], w.alpha, True) - f["L"].astype(np.float64)[:, None])
+    expect = w.alpha * (lp[3] - hp[3])[:, None] * (P @ x["K"])
+    assert metrics.rel_l2(hp[0] - lp[0], expect) < 1e-9
+    assert np.array_equal(lp[2], hp[2])                         # dV does not depend on delta
+
+
 def test_symmetric_values_show_no_bias():
     """Every operation of the dataflow is odd-symmetric, so with V symmetric about zero the
     expected signed error is zero in both variants."""
