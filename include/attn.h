@@ -84,12 +84,44 @@ int attn_fwd_ex(const void* Q, const void* K, const void* V, void* O, float* LSE
                 float beta, float eps, void* stream);
 
 /*
+ * Forward pass with the switches and side outputs of the paper's isolation experiments
+ * (Sec. 3.2, Sec. 3.3.2) and its tie statistics (Sec. 3.3.2, Sec. 4).  Same arithmetic, layouts,
+ * checks and error codes as attn_fwd_ex; in addition
+ *   O_hp         optional (NULL = off) float32 [B,H,N,d]: accumulator / l with NO bf16 rounding,
+ *                i.e. the "O computed in high precision" from which delta_hp is formed
+ *                (attn_delta_hp); O and LSE are written as usual.
+ *   ones_count   optional int32 [B,H,N]: per query row, the number of keys whose P-bar, after
+ *                rounding to bf16, was exactly 1 when it was produced (the precondition of the
+ *                biased rounding, Claim 3).
+ *   fired_count  optional int32 [B,H,N]: per query row, the number of key tiles in which the
+ *                rule of Alg. 3 replaced the row maximum as normaliser (always 0 for the
+ *                standard variant).
+ *   flags        ATTN_FWD_SINGLE_ROUNDING: the unnormalised output is NOT rounded to bf16 before
+ *                the division by l ("computing only O-bar = P-bar V in FP32", Sec. 3.3.2); O is
+ *                still stored as bf16.  Other bits: ATTN_ERR_BAD_ARG.
+ * Optional pointers must be 16-byte aligned and must not alias any other argument.
+ */
+#define ATTN_FWD_SINGLE_ROUNDING 1u
+int attn_fwd_opt(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                 float* O_hp, int* ones_count, int* fired_count,
+                 int B, int H, int N, int d, int causal, float softmax_scale, int variant,
+                 float beta, float eps, unsigned flags, void* stream);
+
+/*
  * delta = rowsum(dO o O)  (Alg. 2, step 4), float32 [B,H,N], from the bf16 O the forward pass
  * stored (the low-precision delta of Claim 1).  Products and the row sum are float32.
  * A pure streaming pass, bound by HBM bandwidth.
  */
 int attn_delta(const void* O, const void* dO, float* delta, int B, int H, int N, int d,
                void* stream);
+
+/*
+ * delta_hp = rowsum(dO o O_hp) from the float32 O_hp of attn_fwd_opt (Sec. 3.2: using the
+ * high-precision output in delta, everything else unchanged, restores stability).  Feed the
+ * result to attn_bwd_dkdv / attn_bwd_dq in place of attn_delta's.
+ */
+int attn_delta_hp(const float* O_hp, const void* dO, float* delta, int B, int H, int N, int d,
+                  void* stream);
 
 /*
  * Backward pass (Alg. 2).

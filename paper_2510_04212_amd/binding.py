@@ -29,8 +29,12 @@ _lib.attn_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _
 _lib.attn_fwd.restype = _i
 _lib.attn_fwd_ex.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _f, _f, _vp]
 _lib.attn_fwd_ex.restype = _i
+_lib.attn_fwd_opt.argtypes = [_vp] * 8 + [_i, _i, _i, _i, _i, _f, _i, _f, _f, ctypes.c_uint, _vp]
+_lib.attn_fwd_opt.restype = _i
 _lib.attn_delta.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp]
 _lib.attn_delta.restype = _i
+_lib.attn_delta_hp.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp]
+_lib.attn_delta_hp.restype = _i
 _lib.attn_bwd.argtypes = [_vp] * 9 + [_vp, _sz, _i, _i, _i, _i, _i, _f, _i, _vp]
 _lib.attn_bwd.restype = _i
 _lib.attn_bwd_dkdv.argtypes = [_vp] * 8 + [_i, _i, _i, _i, _i, _f, _vp]
@@ -44,7 +48,10 @@ _lib.attn_status_string.restype = ctypes.c_char_p
 _lib.attn_fwd_key_tile.argtypes = [_i]
 _lib.attn_fwd_key_tile.restype = _i
 
-EXPORTS = ["attn_fwd", "attn_fwd_ex", "attn_delta", "attn_bwd", "attn_bwd_dkdv", "attn_bwd_dq",
+FWD_SINGLE_ROUNDING = 1
+
+EXPORTS = ["attn_fwd", "attn_fwd_ex", "attn_fwd_opt", "attn_delta", "attn_delta_hp", "attn_bwd",
+           "attn_bwd_dkdv", "attn_bwd_dq",
            "attn_bwd_workspace_bytes",
            "attn_status_string", "attn_fwd_key_tile"]
 
@@ -114,6 +121,44 @@ def attn_fwd(Q, K, V, causal, softmax_scale, variant=STANDARD, beta=None, eps=No
                               float(DEFAULT_EPS if eps is None else eps), _stream(stream))
     _check(st)
     return O, LSE
+
+
+def attn_fwd_opt(Q, K, V, causal, softmax_scale, variant=STANDARD, beta=None, eps=None,
+                 want_O_hp=False, want_counts=False, single_rounding=False,
+                 O=None, LSE=None, stream=None):
+    """attn_fwd_opt of the C ABI: returns a dict with O, LSE and, when asked for, O_hp (float32
+    [B,H,N,d]), ones and fired (int32 [B,H,N])."""
+    B, H, N, d = _bhnd(Q, "Q")
+    for n, t in (("K", K), ("V", V)):
+        if _bhnd(t, n) != (B, H, N, d):
+            raise ValueError(f"{n} shape differs from Q")
+    out = {"O": torch.empty_like(Q) if O is None else O,
+           "LSE": torch.empty((B, H, N), dtype=torch.float32, device=Q.device) if LSE is None else LSE}
+    if want_O_hp:
+        out["O_hp"] = torch.empty((B, H, N, d), dtype=torch.float32, device=Q.device)
+    if want_counts:
+        out["ones"] = torch.empty((B, H, N), dtype=torch.int32, device=Q.device)
+        out["fired"] = torch.empty((B, H, N), dtype=torch.int32, device=Q.device)
+    opt = lambda k: _ptr(out[k]) if k in out else None
+    st = _lib.attn_fwd_opt(_ptr(Q), _ptr(K), _ptr(V), _ptr(out["O"]), _ptr(out["LSE"]), opt("O_hp"),
+                           opt("ones"), opt("fired"), B, H, N, d, int(bool(causal)),
+                           float(softmax_scale), int(variant),
+                           float(DEFAULT_BETA if beta is None else beta),
+                           float(DEFAULT_EPS if eps is None else eps),
+                           FWD_SINGLE_ROUNDING if single_rounding else 0, _stream(stream))
+    _check(st)
+    return out
+
+
+def attn_delta_hp(O_hp, dO, delta=None, stream=None):
+    """delta_hp = rowsum(dO o O_hp), float32 [B,H,N], from the float32 O_hp of attn_fwd_opt."""
+    B, H, N, d = _bhnd(dO, "dO")
+    if O_hp.dtype != torch.float32 or not O_hp.is_cuda or not O_hp.is_contiguous() or tuple(O_hp.shape) != (B, H, N, d):
+        raise ValueError("O_hp must be a contiguous CUDA float32 tensor shaped like dO")
+    if delta is None:
+        delta = torch.empty((B, H, N), dtype=torch.float32, device=dO.device)
+    _check(_lib.attn_delta_hp(_ptr(O_hp), _ptr(dO), _ptr(delta), B, H, N, d, _stream(stream)))
+    return delta
 
 
 def attn_delta(O, dO, delta=None, stream=None):

@@ -5,8 +5,8 @@
 #include "../../include/attn.h"
 
 hipError_t attn_fwd_dispatch(const void*, const void*, const void*, void*, float*, int, int, int,
-                             int, float, int, float, float, hipStream_t);
-hipError_t attn_delta_dispatch(const void*, const void*, float*, long, int, hipStream_t);
+                             int, float, int, float, float, float*, int*, int*, int, hipStream_t);
+hipError_t attn_delta_dispatch(const void*, const void*, float*, long, int, int, hipStream_t);
 hipError_t attn_bwd_dkdv_dispatch(const void*, const void*, const void*, const void*, const float*,
                                   const float*, void*, void*, int, int, int, int, float,
                                   hipStream_t);
@@ -44,10 +44,12 @@ extern "C" const char* attn_status_string(int status) {
   }
 }
 
-extern "C" int attn_fwd_ex(const void* Q, const void* K, const void* V, void* O, float* LSE,
-                           int B, int H, int N, int d, int causal, float softmax_scale,
-                           int variant, float beta, float eps, void* stream) {
+extern "C" int attn_fwd_opt(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                            float* O_hp, int* ones_count, int* fired_count,
+                            int B, int H, int N, int d, int causal, float softmax_scale,
+                            int variant, float beta, float eps, unsigned flags, void* stream) {
   bool empty;
+  if (flags & ~(unsigned)ATTN_FWD_SINGLE_ROUNDING) return ATTN_ERR_BAD_ARG;
   int st = check_shape(B, H, N, d, &empty);
   if (st != ATTN_OK) return st;
   if (variant != ATTN_VARIANT_STANDARD && variant != ATTN_VARIANT_MITIGATED) return ATTN_ERR_BAD_ARG;
@@ -61,9 +63,21 @@ extern "C" int attn_fwd_ex(const void* Q, const void* K, const void* V, void* O,
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE))
     return ATTN_ERR_BAD_ARG;
   if (O == Q || O == K || O == V) return ATTN_ERR_BAD_ARG;
+  if (!aligned16(O_hp) || !aligned16(ones_count) || !aligned16(fired_count)) return ATTN_ERR_BAD_ARG;
+  if (O_hp && (O_hp == Q || O_hp == K || O_hp == V || O_hp == O)) return ATTN_ERR_BAD_ARG;
+  if (ones_count && ones_count == fired_count) return ATTN_ERR_BAD_ARG;
   hipError_t e = attn_fwd_dispatch(Q, K, V, O, LSE, B * H, N, d, causal, softmax_scale, variant,
-                                   beta, eps, static_cast<hipStream_t>(stream));
+                                   beta, eps, O_hp, ones_count, fired_count,
+                                   (flags & ATTN_FWD_SINGLE_ROUNDING) ? 1 : 0,
+                                   static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+extern "C" int attn_fwd_ex(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                           int B, int H, int N, int d, int causal, float softmax_scale,
+                           int variant, float beta, float eps, void* stream) {
+  return attn_fwd_opt(Q, K, V, O, LSE, nullptr, nullptr, nullptr, B, H, N, d, causal,
+                      softmax_scale, variant, beta, eps, 0u, stream);
 }
 
 extern "C" int attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
@@ -73,17 +87,28 @@ extern "C" int attn_fwd(const void* Q, const void* K, const void* V, void* O, fl
                      ATTN_DEFAULT_BETA, ATTN_DEFAULT_EPS, stream);
 }
 
-extern "C" int attn_delta(const void* O, const void* dO, float* delta, int B, int H, int N, int d,
-                          void* stream) {
+static int delta_entry(const void* O, const void* dO, float* delta, int B, int H, int N, int d,
+                       int o_is_f32, void* stream) {
   bool empty;
   int st = check_shape(B, H, N, d, &empty);
   if (st != ATTN_OK) return st;
   if (empty) return ATTN_OK;
   if (!O || !dO || !delta) return ATTN_ERR_NULL;
   if (!aligned16(O) || !aligned16(dO) || !aligned16(delta)) return ATTN_ERR_BAD_ARG;
-  hipError_t e = attn_delta_dispatch(O, dO, delta, (long)B * H * N, d,
+  if (static_cast<const void*>(delta) == O || static_cast<const void*>(delta) == dO) return ATTN_ERR_BAD_ARG;
+  hipError_t e = attn_delta_dispatch(O, dO, delta, (long)B * H * N, d, o_is_f32,
                                      static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+extern "C" int attn_delta(const void* O, const void* dO, float* delta, int B, int H, int N, int d,
+                          void* stream) {
+  return delta_entry(O, dO, delta, B, H, N, d, 0, stream);
+}
+
+extern "C" int attn_delta_hp(const float* O_hp, const void* dO, float* delta, int B, int H, int N,
+                             int d, void* stream) {
+  return delta_entry(O_hp, dO, delta, B, H, N, d, 1, stream);
 }
 
 extern "C" size_t attn_bwd_workspace_bytes(int B, int H, int N, int d) {
@@ -164,7 +189,7 @@ extern "C" int attn_bwd(const void* Q, const void* K, const void* V, const void*
     return ATTN_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   float* delta = static_cast<float*>(workspace);
-  hipError_t e = attn_delta_dispatch(O, dO, delta, (long)B * H * N, d, s);
+  hipError_t e = attn_delta_dispatch(O, dO, delta, (long)B * H * N, d, 0, s);
   if (e != hipSuccess) return ATTN_ERR_LAUNCH;
   e = attn_bwd_dkdv_dispatch(Q, K, V, dO, LSE, delta, dK, dV, B * H, N, d, causal, softmax_scale, s);
   if (e != hipSuccess) return ATTN_ERR_LAUNCH;

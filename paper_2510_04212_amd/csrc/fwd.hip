@@ -18,10 +18,20 @@ namespace {
 constexpr int kBr = 128;   // query rows per work-group
 constexpr int kBc = 64;    // key rows per tile
 
-template <int D, bool CAUSAL, int VARIANT, bool RAGGED>
+// Optional outputs and switches of the forward (the experiments of Sec. 3.2 / 3.3.2 and the
+// tie statistics of Sec. 3.3.2 / 4).  Only kernels instantiated with EXTRAS look at them.
+struct FwdExtras {
+  float* O_hp;          // [B,H,N,d] float32: accumulator / l with no bf16 rounding, or null
+  int* ones;            // [B,H,N]: number of keys whose rounded P-bar was exactly 1, or null
+  int* fired;           // [B,H,N]: number of key tiles in which Alg. 3 moved the normaliser, or null
+  int single_rounding;  // nonzero: O-bar is NOT rounded to bf16 before the division by l
+};
+
+template <int D, bool CAUSAL, int VARIANT, bool RAGGED, bool EXTRAS>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    bf16_t* __restrict__ O, float* __restrict__ LSE, int N, float alpha, float beta, float eps) {
+    bf16_t* __restrict__ O, float* __restrict__ LSE, int N, float alpha, float beta, float eps,
+    FwdExtras ex) {
   constexpr int TILE_BYTES = kBc * D * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   // layout: K buffers [2][TILE_BYTES], then V buffers [2][TILE_BYTES]
@@ -68,6 +78,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
 
+  int ones_cnt = 0, fired_cnt = 0;   // EXTRAS only
   float m = -INFINITY;      // running normaliser, natural-log units of the alpha-scaled scores
   float lsum = 0.f;         // this lane's share of the running row sum (its 32 of the 64 keys per tile)
   const float c2 = alpha * kLog2e;
@@ -145,6 +156,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
         const bool repeated = ((rep >> lane) & 1ull) != 0ull;
         m_prime = (repeated && r_m > 0.f) ? beta * r_m : r_m;
         m_prime = (repeated && r_m < 0.f) ? 0.f : m_prime;
+        if (EXTRAS) fired_cnt += (m_prime != r_m) ? 1 : 0;
       }
       const float m_new = fmaxf(m, m_prime);         // Alg. 1 step 7 / Alg. 3
       const float corr = __builtin_amdgcn_exp2f((m - m_new) * kLog2e);
@@ -166,6 +178,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
             pf[kb][cc][jj] = pp[0];
             pf[kb][cc][jj + 1] = pp[1];
             psum = add_pair_bf16(pp, psum);
+            if (EXTRAS) ones_cnt += ((float)pp[0] == 1.0f ? 1 : 0) + ((float)pp[1] == 1.0f ? 1 : 0);
           }
       lsum = lsum * corr + psum;
       // ---- O^T <- diag(corr) O^T + V_j^T P-bar^T (Alg. 1 step 8)
@@ -195,8 +208,14 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
   // ---- epilogue (Alg. 1 steps 10-13).  Rounding points of Sec. 3.3.2: the unnormalised
   // output is rounded to bf16 first, then divided by l, then rounded again.
   const float l = sum_with_partner32(lsum);
+  int ones_row = 0;
+  if (EXTRAS) {   // the partner lane counted the other 32 keys of every tile
+    auto sw = __builtin_amdgcn_permlane32_swap((unsigned)ones_cnt, (unsigned)ones_cnt, false, false);
+    ones_row = (int)(sw[0] + sw[1]);
+  }
   if (RAGGED && q >= N) return;                            // rows past the sequence end exist only as padding
   bf16_t* Oq = O + head_off + (size_t)q * D;
+  const bool keep_obar_f32 = EXTRAS && ex.single_rounding != 0;
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -204,24 +223,36 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
       bf16x4 o4;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        bf16_t obar = (bf16_t)acc[db][4 * g + e];
-        o4[e] = (bf16_t)((float)obar / l);
+        const float a = acc[db][4 * g + e];
+        const float obar = keep_obar_f32 ? a : (float)(bf16_t)a;
+        o4[e] = (bf16_t)(obar / l);
       }
       *reinterpret_cast<bf16x4*>(Oq + 32 * db + 8 * g + 4 * h) = o4;
+      if (EXTRAS && ex.O_hp != nullptr) {
+        f32x4 hp;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) hp[e] = acc[db][4 * g + e] / l;
+        *reinterpret_cast<f32x4*>(ex.O_hp + head_off + (size_t)q * D + 32 * db + 8 * g + 4 * h) = hp;
+      }
     }
-  if (h == 0) LSE[(size_t)bh * N + q] = m + __logf(l);
+  if (h == 0) {
+    LSE[(size_t)bh * N + q] = m + __logf(l);
+    if (EXTRAS && ex.ones != nullptr) ex.ones[(size_t)bh * N + q] = ones_row;
+    if (EXTRAS && ex.fired != nullptr) ex.fired[(size_t)bh * N + q] = fired_cnt;
+  }
 }
 
 }  // namespace
 
 extern "C" int attn_fwd_key_tile(int d) { return (d == 64 || d == 128) ? kBc : 0; }
 
-template <int D, bool CAUSAL, int VARIANT, bool RAGGED>
+template <int D, bool CAUSAL, int VARIANT, bool RAGGED, bool EXTRAS>
 static hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
-                             int BH, int N, float alpha, float beta, float eps, hipStream_t st) {
+                             int BH, int N, float alpha, float beta, float eps, FwdExtras ex,
+                             hipStream_t st) {
   constexpr int smem = 4 * kBc * D * 2;
   static bool attr_set = false;
-  auto kern = attn_fwd_kernel<D, CAUSAL, VARIANT, RAGGED>;
+  auto kern = attn_fwd_kernel<D, CAUSAL, VARIANT, RAGGED, EXTRAS>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -230,18 +261,25 @@ static hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* 
   }
   dim3 grid(BH * ((N + kBr - 1) / kBr));
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, (const bf16_t*)Q, (const bf16_t*)K,
-                     (const bf16_t*)V, (bf16_t*)O, LSE, N, alpha, beta, eps);
+                     (const bf16_t*)V, (bf16_t*)O, LSE, N, alpha, beta, eps, ex);
   return hipGetLastError();
 }
 
 // Host-side dispatch used by the C ABI (api.hip).  Shapes are validated by the caller.
+// The optional outputs / switches select a second set of kernels (always the bounds-checking
+// instantiation), so that the plain forward carries none of their instructions.
 hipError_t attn_fwd_dispatch(const void* Q, const void* K, const void* V, void* O, float* LSE,
                              int BH, int N, int d, int causal, float alpha, int variant,
-                             float beta, float eps, hipStream_t st) {
-#define CASE(DD, CC, VV)                                                                     \
-  if (d == DD && (causal != 0) == CC && variant == VV)                                        \
-    return (N % kBr) ? launch_fwd<DD, CC, VV, true>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, st) \
-                     : launch_fwd<DD, CC, VV, false>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, st);
+                             float beta, float eps, float* O_hp, int* ones, int* fired,
+                             int single_rounding, hipStream_t st) {
+  const bool extras = O_hp != nullptr || ones != nullptr || fired != nullptr || single_rounding != 0;
+  const FwdExtras ex{O_hp, ones, fired, single_rounding};
+#define CASE(DD, CC, VV)                                                                      \
+  if (d == DD && (causal != 0) == CC && variant == VV) {                                       \
+    if (extras) return launch_fwd<DD, CC, VV, true, true>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, st); \
+    return (N % kBr) ? launch_fwd<DD, CC, VV, true, false>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, st) \
+                     : launch_fwd<DD, CC, VV, false, false>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, st); \
+  }
   CASE(64, false, 0) CASE(64, false, 1) CASE(64, true, 0) CASE(64, true, 1)
   CASE(128, false, 0) CASE(128, false, 1) CASE(128, true, 0) CASE(128, true, 1)
 #undef CASE

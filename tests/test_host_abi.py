@@ -67,6 +67,16 @@ def test_argument_validation_happens_on_the_host(binding):
     assert fwd(None, None, None, None, None, 0, 5, 128, 64) == OK      # empty batch: no-op
     ex = lambda beta, eps: lib.attn_fwd_ex(q, p, p, p, p, 1, 1, 128, 64, 1, 0.125, 1, beta, eps, None)
     assert ex(1.0, 1e-3) == BAD and ex(2.0, -1.0) == BAD and ex(float("nan"), 1e-3) == BAD
+    opt = lambda ohp, ones, fired, flags=0, O=q: lib.attn_fwd_opt(p, p, p, O, p, ohp, ones, fired, 1, 1, 128, 64, 1, 0.125, 0, 2.0, 1e-3, flags, None)
+    assert opt(None, None, None, flags=2) == BAD                 # unknown flag bit
+    assert opt(mis, None, None) == BAD                           # misaligned optional output
+    assert opt(q, None, None) == BAD                             # O_hp aliases O
+    r_ = ctypes.c_void_p(0x3000)
+    assert opt(None, r_, r_) == BAD                              # the two count outputs alias
+    assert lib.attn_fwd_opt(p, p, p, q, p, None, None, None, 1, 1, 128, 96, 1, 0.125, 0, 2.0, 1e-3, 0, None) == UNSUP
+    assert lib.attn_delta_hp(None, p, q, 1, 1, 128, 64, None) == NULL
+    assert lib.attn_delta_hp(p, p, p, 1, 1, 128, 64, None) == BAD  # delta aliases an input
+    assert lib.attn_delta_hp(None, None, None, 0, 3, 128, 64, None) == OK
     assert lib.attn_delta(None, p, p, 1, 1, 128, 64, None) == NULL
     assert lib.attn_delta(p, p, p, 1, 1, 130, 32, None) == UNSUP
     assert lib.attn_delta(None, None, None, 2, 0, 128, 64, None) == OK
