@@ -124,6 +124,17 @@ int attn_delta_hp(const float* O_hp, const void* dO, float* delta, int B, int H,
                   void* stream);
 
 /*
+ * delta = rowsum(P o dP) with P = exp(alpha Q K^T - LSE) and dP = dO V^T recomputed in float32
+ * (Sec. 3.2: recomputing the output inside the backward pass instead of reading the forward's
+ * bf16 O stabilises training; rowsum(P o dP) = rowsum(dO o (P V)) is that quantity without ever
+ * forming O).  Costs two of the backward's matrix products again.  Inputs as for attn_bwd_dq;
+ * delta float32 [B,H,N] is written.  Feed it to attn_bwd_dkdv / attn_bwd_dq.
+ */
+int attn_delta_recompute(const void* Q, const void* K, const void* V, const void* dO,
+                         const float* LSE, float* delta, int B, int H, int N, int d, int causal,
+                         float softmax_scale, void* stream);
+
+/*
  * Backward pass (Alg. 2).
  *   in : Q, K, V, O, dO  bf16 [B,H,N,d];  LSE float32 [B,H,N] from attn_fwd
  *   out: dQ, dK, dV      bf16 [B,H,N,d]

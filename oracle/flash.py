@@ -171,6 +171,26 @@ def backward(Q, K, V, O, dO, L, alpha, causal, Bc=None, Br=None, prec=BF16):
     return dQ, dK, dV, delta
 
 
+def delta_recomputed(Q, K, V, dO, L, alpha, causal, Bc=None, prec=BF16):
+    """delta = rowsum(P o dP) with P = exp(S - L), dP = dO V^T, accumulated over key tiles in
+    working precision, nothing rounded (Sec. 3.2: recomputing the output in the backward pass
+    instead of reading the forward's bf16 O; rowsum(P o dP) = rowsum(dO o (P V)))."""
+    dt = prec.dtype
+    Qw = np.asarray(Q, dtype=dt); Kw = np.asarray(K, dtype=dt); Vw = np.asarray(V, dtype=dt)
+    dOw = np.asarray(dO, dtype=dt); Lw = np.asarray(L, dtype=dt)
+    N = Qw.shape[0]
+    Bc = N if Bc is None else int(Bc)
+    delta = np.zeros(N, dtype=dt)
+    with np.errstate(invalid="ignore", over="ignore"):
+        for k0 in range(0, N, Bc):
+            Kj = Kw[k0:k0 + Bc]; Vj = Vw[k0:k0 + Bc]
+            S = _tile_scores(Qw, Kj, alpha, causal, k0, prec)
+            P = np.exp(S - Lw[:, None]).astype(dt)
+            dP = (dOw @ Vj.T).astype(dt)
+            delta = (delta + np.sum(P * dP, axis=1, dtype=dt)).astype(dt)
+    return delta
+
+
 def forward_backward_bh(Q, K, V, dO, alpha, causal, variant=STANDARD, beta=2.0, eps=1e-3,
                         Bc=None, prec=BF16, heads=None):
     """[B,H,N,d] wrapper over forward() then backward(); see oracle.exact.forward_backward_bh."""

@@ -35,6 +35,8 @@ _lib.attn_delta.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp]
 _lib.attn_delta.restype = _i
 _lib.attn_delta_hp.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp]
 _lib.attn_delta_hp.restype = _i
+_lib.attn_delta_recompute.argtypes = [_vp] * 6 + [_i, _i, _i, _i, _i, _f, _vp]
+_lib.attn_delta_recompute.restype = _i
 _lib.attn_bwd.argtypes = [_vp] * 9 + [_vp, _sz, _i, _i, _i, _i, _i, _f, _i, _vp]
 _lib.attn_bwd.restype = _i
 _lib.attn_bwd_dkdv.argtypes = [_vp] * 8 + [_i, _i, _i, _i, _i, _f, _vp]
@@ -50,7 +52,8 @@ _lib.attn_fwd_key_tile.restype = _i
 
 FWD_SINGLE_ROUNDING = 1
 
-EXPORTS = ["attn_fwd", "attn_fwd_ex", "attn_fwd_opt", "attn_delta", "attn_delta_hp", "attn_bwd",
+EXPORTS = ["attn_fwd", "attn_fwd_ex", "attn_fwd_opt", "attn_delta", "attn_delta_hp",
+           "attn_delta_recompute", "attn_bwd",
            "attn_bwd_dkdv", "attn_bwd_dq",
            "attn_bwd_workspace_bytes",
            "attn_status_string", "attn_fwd_key_tile"]
@@ -158,6 +161,20 @@ def attn_delta_hp(O_hp, dO, delta=None, stream=None):
     if delta is None:
         delta = torch.empty((B, H, N), dtype=torch.float32, device=dO.device)
     _check(_lib.attn_delta_hp(_ptr(O_hp), _ptr(dO), _ptr(delta), B, H, N, d, _stream(stream)))
+    return delta
+
+
+def attn_delta_recompute(Q, K, V, dO, LSE, causal, softmax_scale, delta=None, stream=None):
+    """delta = rowsum(P o dP), recomputed in float32 from Q, K, V, dO and LSE."""
+    B, H, N, d = _bhnd(Q, "Q")
+    for n, t in (("K", K), ("V", V), ("dO", dO)):
+        if _bhnd(t, n) != (B, H, N, d):
+            raise ValueError(f"{n} shape differs from Q")
+    if delta is None:
+        delta = torch.empty((B, H, N), dtype=torch.float32, device=Q.device)
+    _check(_lib.attn_delta_recompute(_ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(LSE), _ptr(delta),
+                                     B, H, N, d, int(bool(causal)), float(softmax_scale),
+                                     _stream(stream)))
     return delta
 
 

@@ -12,6 +12,9 @@ hipError_t attn_bwd_dkdv_dispatch(const void*, const void*, const void*, const v
                                   hipStream_t);
 hipError_t attn_bwd_dq_dispatch(const void*, const void*, const void*, const void*, const float*,
                                 const float*, void*, int, int, int, int, float, hipStream_t);
+hipError_t attn_delta_recompute_dispatch(const void*, const void*, const void*, const void*,
+                                         const float*, float*, int, int, int, int, float,
+                                         hipStream_t);
 
 namespace {
 
@@ -194,5 +197,23 @@ extern "C" int attn_bwd(const void* Q, const void* K, const void* V, const void*
   e = attn_bwd_dkdv_dispatch(Q, K, V, dO, LSE, delta, dK, dV, B * H, N, d, causal, softmax_scale, s);
   if (e != hipSuccess) return ATTN_ERR_LAUNCH;
   e = attn_bwd_dq_dispatch(Q, K, V, dO, LSE, delta, dQ, B * H, N, d, causal, softmax_scale, s);
+  return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+extern "C" int attn_delta_recompute(const void* Q, const void* K, const void* V, const void* dO,
+                                    const float* LSE, float* delta, int B, int H, int N, int d,
+                                    int causal, float softmax_scale, void* stream) {
+  bool empty;
+  int st = check_bwd_common(B, H, N, d, softmax_scale, &empty);
+  if (st != ATTN_OK) return st;
+  if (empty) return ATTN_OK;
+  if (!Q || !K || !V || !dO || !LSE || !delta) return ATTN_ERR_NULL;
+  const void* ptrs[] = {Q, K, V, dO, LSE, delta};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return ATTN_ERR_BAD_ARG;
+  for (int i = 0; i < 5; ++i)
+    if (ptrs[i] == static_cast<const void*>(delta)) return ATTN_ERR_BAD_ARG;
+  hipError_t e = attn_delta_recompute_dispatch(Q, K, V, dO, LSE, delta, B * H, N, d, causal,
+                                               softmax_scale, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
 }

@@ -301,11 +301,14 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
   }
 }
 
-template <int D, bool CAUSAL, bool RAGGED>
+// DELTA_MODE: instead of dQ the kernel forms delta = rowsum(P o dP) (the recomputed,
+// float32 form of delta of Sec. 3.2: mathematically rowsum(dO o O), but free of the forward's
+// bf16 roundings of O); `delta` is not read, `delta_out` receives the result, dQ is not touched.
+template <int D, bool CAUSAL, bool RAGGED, bool DELTA_MODE>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
-    bf16_t* __restrict__ dQ, int N, float alpha) {
+    bf16_t* __restrict__ dQ, float* __restrict__ delta_out, int N, float alpha) {
   constexpr int TILE_BYTES = kKTile * D * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* ldsK = smem;
@@ -336,7 +339,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     dof[kc] = *reinterpret_cast<const bf16x8*>(dO + head_off + (size_t)qc * D + 16 * kc + 8 * h);
   }
   const float l2 = LSE[(size_t)bh * N + qc] * kLog2e;
-  const float dl = delta[(size_t)bh * N + qc];
+  const float dl = DELTA_MODE ? 0.f : delta[(size_t)bh * N + qc];
+  float pdp = 0.f;                                   // DELTA_MODE: this lane's share of sum_k P dP
   // -delta_i in all 16 accumulator slots of the lane: the third operand of the first dP^T matrix
   // instruction of every key block, which then delivers dP - delta with no vector instruction
   // (Alg. 2 step 12).  Kept opaque so that it stays resident instead of being rebuilt per block.
@@ -400,16 +404,19 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
             int key = kb0 + 8 * (i >> 2) + 4 * h + (i & 3);
             if (key > q) p = 0.f;
           }
-          dsf[i >> 3][i & 7] = (bf16_t)(p * dp[i]);      // dp already holds dP - delta
+          if (DELTA_MODE) pdp = __builtin_fmaf(p, dp[i], pdp);
+          else dsf[i >> 3][i & 7] = (bf16_t)(p * dp[i]);      // dp already holds dP - delta
         }
-        // ---- dQ_i^T += K_j^T dS^T (step 13)
+        if (!DELTA_MODE) {
+          // ---- dQ_i^T += K_j^T dS^T (step 13)
 #pragma unroll
-        for (int cc = 0; cc < 2; ++cc)
+          for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
-          for (int db = 0; db < D / 32; ++db) {
-            dQt[db] = mfma32(lds_read_col8<D>(tK, 32 * kb + 16 * cc, 32 * db, lane), dsf[cc], dQt[db]);
-          }
-        sched_reads_ahead_of_mfma<D / 16, 2, 4>();
+            for (int db = 0; db < D / 32; ++db) {
+              dQt[db] = mfma32(lds_read_col8<D>(tK, 32 * kb + 16 * cc, 32 * db, lane), dsf[cc], dQt[db]);
+            }
+          sched_reads_ahead_of_mfma<D / 16, 2, 4>();
+        }
       };
 #pragma unroll
       for (int kb = 0; kb < kKTile / 32; ++kb) {
@@ -422,6 +429,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     }
     wait_vmem();
     __syncthreads();
+  }
+  if (DELTA_MODE) {
+    const float dsum = sum_with_partner32(pdp);      // the partner lane holds the other keys of every block
+    if (h == 0 && (!RAGGED || qw + r < N)) delta_out[(size_t)bh * N + qw + r] = dsum;
+    return;
   }
   if (!RAGGED || qw + r < N) store_acc_T<D>(dQ + head_off + (size_t)(qw + r) * D, dQt, alpha, h);
 }
@@ -450,18 +462,18 @@ static hipError_t launch_dkdv(const void* Q, const void* K, const void* V, const
   return hipGetLastError();
 }
 
-template <int D, bool CAUSAL, bool RAGGED>
+template <int D, bool CAUSAL, bool RAGGED, bool DELTA_MODE>
 static hipError_t launch_dq(const void* Q, const void* K, const void* V, const void* dO,
-                            const float* LSE, const float* delta, void* dQ, int BH, int N,
-                            float alpha, hipStream_t st) {
+                            const float* LSE, const float* delta, void* dQ, float* delta_out,
+                            int BH, int N, float alpha, hipStream_t st) {
   constexpr int smem = 4 * kKTile * D * 2;
   static bool set = false;
-  auto k = attn_bwd_dq_kernel<D, CAUSAL, RAGGED>;
+  auto k = attn_bwd_dq_kernel<D, CAUSAL, RAGGED, DELTA_MODE>;
   hipError_t e;
   if ((e = set_smem(k, smem, set)) != hipSuccess) return e;
   hipLaunchKernelGGL(k, dim3(BH * ((N + kQPerWG - 1) / kQPerWG)), dim3(256), smem, st, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
-                     (bf16_t*)dQ, N, alpha);
+                     (bf16_t*)dQ, delta_out, N, alpha);
   return hipGetLastError();
 }
 
@@ -486,9 +498,22 @@ hipError_t attn_bwd_dq_dispatch(const void* Q, const void* K, const void* V, con
   const bool ragged = (N % kQPerWG) != 0;
 #define CASE(DD, CC, RR)                                                \
   if (d == DD && (causal != 0) == CC && ragged == RR)                   \
-    return launch_dq<DD, CC, RR>(Q, K, V, dO, LSE, delta, dQ, BH, N, alpha, st);
+    return launch_dq<DD, CC, RR, false>(Q, K, V, dO, LSE, delta, dQ, nullptr, BH, N, alpha, st);
   CASE(64, false, false) CASE(64, false, true) CASE(64, true, false) CASE(64, true, true)
   CASE(128, false, false) CASE(128, false, true) CASE(128, true, false) CASE(128, true, true)
+#undef CASE
+  return hipErrorInvalidValue;
+}
+
+// delta = rowsum(P o dP) recomputed from Q, K, V, dO and LSE (always the bounds-checking kernels).
+hipError_t attn_delta_recompute_dispatch(const void* Q, const void* K, const void* V,
+                                         const void* dO, const float* LSE, float* delta_out,
+                                         int BH, int N, int d, int causal, float alpha,
+                                         hipStream_t st) {
+#define CASE(DD, CC)                                  \
+  if (d == DD && (causal != 0) == CC)                 \
+    return launch_dq<DD, CC, true, true>(Q, K, V, dO, LSE, nullptr, nullptr, delta_out, BH, N, alpha, st);
+  CASE(64, false) CASE(64, true) CASE(128, false) CASE(128, true)
 #undef CASE
   return hipErrorInvalidValue;
 }

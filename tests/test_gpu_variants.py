@@ -162,3 +162,55 @@ def test_counts_against_the_emulation(lib, name):
             if v == 0:
                 assert int(fired.sum()) == 0
                 assert (ones >= 1).all()        # the running maximum itself always has P-bar = 1 at least once
+
+
+@pytest.mark.parametrize("name,heads", [("tiny", [(0, 0)]), ("gpt2s", [(0, 0), (5, 3)]), ("pairs_skew", [(0, 0), (3, 11)])])
+def test_recomputed_delta(lib, name, heads):
+    """attn_delta_recompute: rowsum(P o dP) against the fp64 delta and against its emulation;
+    on the one-signed paired-key input it carries none of the bias of delta_lp."""
+    w = synth.WORKLOADS[name]
+    x = synth.make(w, DEV)
+    O, L = lib.attn_fwd(x["Q"], x["K"], x["V"], w.causal, w.alpha, 0)
+    d_rc = lib.attn_delta_recompute(x["Q"], x["K"], x["V"], x["dO"], L, w.causal, w.alpha)
+    d_lp = lib.attn_delta(O, x["dO"])
+    torch.cuda.synchronize()
+    assert torch.isfinite(d_rc).all()
+    e_rc, e_lp = [], []
+    for (b, h) in heads:
+        xs = head_np(x, b, h)
+        O64, L64 = exact.forward(xs["Q"], xs["K"], xs["V"], w.alpha, w.causal)
+        d64 = np.sum(xs["dO"] * O64, axis=1)
+        emu = flash.delta_recomputed(xs["Q"], xs["K"], xs["V"], xs["dO"], _np(L[b, h]), w.alpha, w.causal, Bc=64)
+        got = _np(d_rc[b, h])
+        scale = 1 + np.abs(d64).max()
+        assert np.abs(got - emu).max() <= 2e-4 * scale          # float32 reassociation + exp2 vs exp
+        assert np.abs(got - d64).max() <= 5e-3 * scale          # float32 L of the bf16 forward
+        e_rc.append(got - d64); e_lp.append(_np(d_lp[b, h]) - d64)
+    if name == "pairs_skew":
+        e_rc, e_lp = np.concatenate(e_rc), np.concatenate(e_lp)
+        assert e_lp.mean() > 0 and abs(e_rc.mean()) < e_lp.mean() / 10
+
+
+def test_backward_from_each_delta(lib):
+    """The three deltas (from bf16 O, from O_hp, recomputed) fed to the same two backward stages:
+    each set of gradients meets the tolerance against fp64; dV does not depend on delta."""
+    w = synth.WORKLOADS["gpt2s"]
+    x = synth.make(w, DEV)
+    r = lib.attn_fwd_opt(x["Q"], x["K"], x["V"], w.causal, w.alpha, 0, want_O_hp=True)
+    deltas = {"lp": lib.attn_delta(r["O"], x["dO"]), "hp": lib.attn_delta_hp(r["O_hp"], x["dO"]),
+              "rc": lib.attn_delta_recompute(x["Q"], x["K"], x["V"], x["dO"], r["LSE"], w.causal, w.alpha)}
+    grads = {}
+    for k, dl in deltas.items():
+        dK, dV = lib.attn_bwd_dkdv(x["Q"], x["K"], x["V"], x["dO"], r["LSE"], dl, w.causal, w.alpha)
+        dQ = lib.attn_bwd_dq(x["Q"], x["K"], x["V"], x["dO"], r["LSE"], dl, w.causal, w.alpha)
+        grads[k] = {"dQ": dQ, "dK": dK, "dV": dV}
+    torch.cuda.synchronize()
+    assert torch.equal(grads["lp"]["dV"], grads["hp"]["dV"]) and torch.equal(grads["lp"]["dV"], grads["rc"]["dV"])
+    b, h = 2, 9
+    xs = head_np(x, b, h)
+    ref = exact.forward_backward(xs["Q"], xs["K"], xs["V"], xs["dO"], w.alpha, w.causal)
+    for k in grads:
+        for name, rr in (("dQ", ref[2]), ("dK", ref[3]), ("dV", ref[4])):
+            got = _np(grads[k][name][b, h])
+            assert metrics.rel_l2(got, rr) <= TOL_REL, (k, name)
+            assert metrics.max_abs(got, rr) <= 1.25 * TOL_ABS, (k, name)

@@ -77,6 +77,9 @@ def test_argument_validation_happens_on_the_host(binding):
     assert lib.attn_delta_hp(None, p, q, 1, 1, 128, 64, None) == NULL
     assert lib.attn_delta_hp(p, p, p, 1, 1, 128, 64, None) == BAD  # delta aliases an input
     assert lib.attn_delta_hp(None, None, None, 0, 3, 128, 64, None) == OK
+    rc = lambda *a: lib.attn_delta_recompute(*a, 1, 1, 128, 64, 1, 0.125, None)
+    assert rc(p, p, p, p, p, None) == NULL and rc(p, p, p, p, p, p) == BAD and rc(p, p, p, mis, p, q) == BAD
+    assert lib.attn_delta_recompute(p, p, p, p, p, q, 1, 1, 128, 64, 1, -1.0, None) == BAD
     assert lib.attn_delta(None, p, p, 1, 1, 128, 64, None) == NULL
     assert lib.attn_delta(p, p, p, 1, 1, 130, 32, None) == UNSUP
     assert lib.attn_delta(None, None, None, 2, 0, 128, 64, None) == OK

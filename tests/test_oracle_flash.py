@@ -201,6 +201,29 @@ def test_high_precision_output_variants_of_sec_3_2():
     assert np.array_equal(lp[2], hp[2])                         # dV does not depend on delta
 
 
+def test_recomputed_delta():
+    """rowsum(P o dP) = rowsum(dO o O) exactly in real arithmetic (Sec. 3.1); in the bf16 dataflow
+    the recomputed form has none of the bias that delta_lp inherits from the rounded O."""
+    Q, K, V, dO = _rand(11, 96, 32, 1.3)
+    for causal in (False, True):
+        O, L = exact.forward(Q, K, V, 0.2, causal)
+        want = np.sum(dO * O, axis=1)
+        for Bc in (None, 32, 40):
+            got = flash.delta_recomputed(Q, K, V, dO, L, 0.2, causal, Bc=Bc, prec=flash.FP64)
+            assert np.max(np.abs(got - want)) < 1e-12 * (1 + np.max(np.abs(want)))
+    w = synth.WORKLOADS["pairs_skew"]
+    e_lp, e_rc = [], []
+    for h in range(3):
+        x = synth.head_f64(w, 0, h)
+        O, _ = exact.forward(x["Q"], x["K"], x["V"], w.alpha, True)
+        d_exact = np.sum(x["dO"] * O, axis=1)
+        f = flash.forward(x["Q"], x["K"], x["V"], w.alpha, True, 0, Bc=64)
+        e_lp.append(np.sum(x["dO"] * f["O"], axis=1) - d_exact)
+        e_rc.append(flash.delta_recomputed(x["Q"], x["K"], x["V"], x["dO"], f["L"], w.alpha, True, Bc=64) - d_exact)
+    e_lp, e_rc = np.concatenate(e_lp), np.concatenate(e_rc)
+    assert e_lp.mean() > 0 and abs(e_rc.mean()) < e_lp.mean() / 10
+
+
 def test_symmetric_values_show_no_bias():
     """Every operation of the dataflow is odd-symmetric, so with V symmetric about zero the
     expected signed error is zero in both variants."""
