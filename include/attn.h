@@ -49,8 +49,15 @@ typedef enum {
 
 enum {
   ATTN_VARIANT_STANDARD = 0,  /* Alg. 1: safe softmax, normaliser = running row maximum */
-  ATTN_VARIANT_MITIGATED = 1  /* Alg. 3: normaliser beta*r_m (r_m > 0) or 0 (r_m < 0) whenever a
+  ATTN_VARIANT_MITIGATED = 1, /* Alg. 3: normaliser beta*r_m (r_m > 0) or 0 (r_m < 0) whenever a
                                  key tile's row maximum r_m is attained (within eps) more than once */
+  ATTN_VARIANT_MITIGATED_ROW = 2 /* the same rule applied to the WHOLE row (the paper's untiled
+                                 form, Sec. 4: r_m and the count are taken over all keys), so the
+                                 result does not depend on the key-tile size.  Two passes: the two
+                                 largest scores of every row are found first (a repeated maximum
+                                 <=> the second largest lies within eps of the largest), then the
+                                 forward runs with that fixed normaliser.  Costs one extra
+                                 Q K^T product; LSE[] is used as scratch between the passes. */
 };
 
 /* Default parameters of the stabilised forward (Sec. 4: beta in [2,8], beta = 2 in the paper's

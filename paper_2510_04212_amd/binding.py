@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libattn_gfx950.so")
 
 STANDARD = 0
 MITIGATED = 1
+MITIGATED_ROW = 2
 DEFAULT_BETA = 2.0
 DEFAULT_EPS = 1e-3
 

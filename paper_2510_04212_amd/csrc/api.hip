@@ -55,9 +55,9 @@ extern "C" int attn_fwd_opt(const void* Q, const void* K, const void* V, void* O
   if (flags & ~(unsigned)ATTN_FWD_SINGLE_ROUNDING) return ATTN_ERR_BAD_ARG;
   int st = check_shape(B, H, N, d, &empty);
   if (st != ATTN_OK) return st;
-  if (variant != ATTN_VARIANT_STANDARD && variant != ATTN_VARIANT_MITIGATED) return ATTN_ERR_BAD_ARG;
+  if (variant < ATTN_VARIANT_STANDARD || variant > ATTN_VARIANT_MITIGATED_ROW) return ATTN_ERR_BAD_ARG;
   if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale)) return ATTN_ERR_BAD_ARG;
-  if (variant == ATTN_VARIANT_MITIGATED) {
+  if (variant != ATTN_VARIANT_STANDARD) {
     if (!(beta > 1.f) || !std::isfinite(beta)) return ATTN_ERR_BAD_ARG;
     if (!(eps >= 0.f) || !std::isfinite(eps)) return ATTN_ERR_BAD_ARG;
   }
@@ -175,7 +175,7 @@ extern "C" int attn_bwd(const void* Q, const void* K, const void* V, const void*
   bool empty;
   int st = check_shape(B, H, N, d, &empty);
   if (st != ATTN_OK) return st;
-  if (variant != ATTN_VARIANT_STANDARD && variant != ATTN_VARIANT_MITIGATED) return ATTN_ERR_BAD_ARG;
+  if (variant < ATTN_VARIANT_STANDARD || variant > ATTN_VARIANT_MITIGATED_ROW) return ATTN_ERR_BAD_ARG;
   if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale)) return ATTN_ERR_BAD_ARG;
   if (empty) return ATTN_OK;
   if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_NULL;

@@ -27,6 +27,16 @@ struct FwdExtras {
   int single_rounding;  // nonzero: O-bar is NOT rounded to bf16 before the division by l
 };
 
+// VARIANT: 0 = Alg. 1, 1 = Alg. 3 (repeated maximum looked for inside each key tile, as the
+// algorithm is written), and the two passes of the tile-size-independent form of Alg. 3
+// (the rule of Sec. 4 applied to the whole row, as in the paper's untiled analysis):
+//   kRowStats   scores only; per row the two largest scores over ALL keys decide the normaliser
+//               (a repeated maximum <=> the second largest is within eps of the largest), which
+//               is written to LSE[] as a scratch value;
+//   kFixedNorm  the forward with that fixed per-row normaliser read back from LSE[] (no running
+//               maximum, no accumulator rescale), LSE[] then receives m + log l as usual.
+constexpr int kRowStats = 3, kFixedNorm = 2;
+
 template <int D, bool CAUSAL, int VARIANT, bool RAGGED, bool EXTRAS>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
@@ -64,7 +74,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
   const int kend = CAUSAL ? ((RAGGED && q0 + kBr > N) ? N : q0 + kBr) : N;   // keys [0, kend) can matter to this block
   const int ntiles = RAGGED ? (kend + kBc - 1) / kBc : kend / kBc;
   loader.template load_rows<RAGGED>(smem, Kh, 0, N, tid);
-  loader.template load_rows<RAGGED>(smem + 2 * TILE_BYTES, Vh, 0, N, tid);
+  if (VARIANT != kRowStats) loader.template load_rows<RAGGED>(smem + 2 * TILE_BYTES, Vh, 0, N, tid);
 
   // Q_i^T fragments: lane (r,h) holds Q[qw + r][16kc + 8h .. +7] for every kc.
   bf16x8 qf[D / 16];
@@ -79,7 +89,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
     for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
 
   int ones_cnt = 0, fired_cnt = 0;   // EXTRAS only
-  float m = -INFINITY;      // running normaliser, natural-log units of the alpha-scaled scores
+  float top1 = -INFINITY, top2 = -INFINITY;   // kRowStats: the lane's two largest raw scores so far
+  // running normaliser, natural-log units of the alpha-scaled scores (kFixedNorm: the row's
+  // normaliser chosen by the kRowStats pass)
+  float m = (VARIANT == kFixedNorm) ? LSE[(size_t)bh * N + qc] : -INFINITY;
   float lsum = 0.f;         // this lane's share of the running row sum (its 32 of the 64 keys per tile)
   const float c2 = alpha * kLog2e;
   // Alg. 3's test  r_m - alpha*s <= eps  in terms of the raw score s:  s >= (r_m - eps) / alpha
@@ -96,7 +109,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
     const char* tV = smem + (2 + BUF) * TILE_BYTES;
     if (j + 1 < ntiles) {   // lands in the other buffer while this tile is being processed
       loader.template load_rows<RAGGED>(smem + (BUF ^ 1) * TILE_BYTES, Kh, (j + 1) * kBc, N, tid);
-      loader.template load_rows<RAGGED>(smem + (2 + (BUF ^ 1)) * TILE_BYTES, Vh, (j + 1) * kBc, N, tid);
+      if (VARIANT != kRowStats)
+        loader.template load_rows<RAGGED>(smem + (2 + (BUF ^ 1)) * TILE_BYTES, Vh, (j + 1) * kBc, N, tid);
     }
     const int k0 = j * kBc;
     // A wave whose 32 rows all lie above this key tile has nothing to do in it (causal).
@@ -124,6 +138,21 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
             if ((CAUSAL && key > q) || (RAGGED && key >= N)) s[kb][i] = -INFINITY;
           }
       }
+      if (VARIANT == kRowStats) {
+        // two largest values seen by this lane (duplicates count: a value met twice is both)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            top2 = __builtin_amdgcn_fmed3f(top1, top2, s[kb][i]);
+            top1 = fmaxf(top1, s[kb][i]);
+          }
+      } else {
+      float corr = 1.f;
+      float mneg;
+      if (VARIANT == kFixedNorm) {
+        mneg = -m * kLog2e;
+      } else {
       // ---- tile row maximum r_m (of the alpha-scaled scores)
       float mx = s[0][0];
 #pragma unroll
@@ -159,9 +188,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
         if (EXTRAS) fired_cnt += (m_prime != r_m) ? 1 : 0;
       }
       const float m_new = fmaxf(m, m_prime);         // Alg. 1 step 7 / Alg. 3
-      const float corr = __builtin_amdgcn_exp2f((m - m_new) * kLog2e);
+      corr = __builtin_amdgcn_exp2f((m - m_new) * kLog2e);
       m = m_new;
-      const float mneg = -m_new * kLog2e;
+      mneg = -m_new * kLog2e;
+      }
       // ---- P-bar = exp(S - m), rounded to bf16; row sum of the ROUNDED values
       bf16x8 pf[2][2];
       float psum = 0.f;
@@ -182,7 +212,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
           }
       lsum = lsum * corr + psum;
       // ---- O^T <- diag(corr) O^T + V_j^T P-bar^T (Alg. 1 step 8)
-      if (__builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {
+      if (VARIANT != kFixedNorm && __builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -195,6 +225,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
 #pragma unroll
           for (int db = 0; db < D / 32; ++db)
             acc[db] = mfma32(lds_col8<D>(tV, fo, 32 * kb + 16 * cc, db), pf[kb][cc], acc[db]);
+      }
     }
     wait_vmem();
     __syncthreads();
@@ -205,6 +236,21 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
     if (j + 1 < ntiles) tile_step(std::integral_constant<int, 1>{}, j + 1);
   }
 
+  if (VARIANT == kRowStats) {
+    // merge the two lanes of a row, then the rule of Sec. 4 on the whole row
+    const float o1 = partner32(top1), o2 = partner32(top2);
+    const float M1 = fmaxf(top1, o1);
+    const float M2 = fmaxf(fminf(top1, o1), fmaxf(top2, o2));
+    const float r_m = M1 * alpha;
+    const bool repeated = (r_m - M2 * alpha) <= eps;      // r_s > 1
+    float m_row = (repeated && r_m > 0.f) ? beta * r_m : r_m;
+    m_row = (repeated && r_m < 0.f) ? 0.f : m_row;
+    if (h == 0 && (!RAGGED || q < N)) {
+      LSE[(size_t)bh * N + q] = m_row;
+      if (EXTRAS && ex.fired != nullptr) ex.fired[(size_t)bh * N + q] = (m_row != r_m) ? 1 : 0;
+    }
+    return;
+  }
   // ---- epilogue (Alg. 1 steps 10-13).  Rounding points of Sec. 3.3.2: the unnormalised
   // output is rounded to bf16 first, then divided by l, then rounded again.
   const float l = sum_with_partner32(lsum);
@@ -238,7 +284,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
   if (h == 0) {
     LSE[(size_t)bh * N + q] = m + __logf(l);
     if (EXTRAS && ex.ones != nullptr) ex.ones[(size_t)bh * N + q] = ones_row;
-    if (EXTRAS && ex.fired != nullptr) ex.fired[(size_t)bh * N + q] = fired_cnt;
+    if (EXTRAS && VARIANT != kFixedNorm && ex.fired != nullptr) ex.fired[(size_t)bh * N + q] = fired_cnt;
   }
 }
 
@@ -274,6 +320,17 @@ hipError_t attn_fwd_dispatch(const void* Q, const void* K, const void* V, void* 
                              int single_rounding, hipStream_t st) {
   const bool extras = O_hp != nullptr || ones != nullptr || fired != nullptr || single_rounding != 0;
   const FwdExtras ex{O_hp, ones, fired, single_rounding};
+  if (variant == 2) {   // whole-row detection: statistics pass, then the fixed-normaliser pass
+#define CASE2(DD, CC)                                                                           \
+  if (d == DD && (causal != 0) == CC) {                                                          \
+    hipError_t e = launch_fwd<DD, CC, kRowStats, true, true>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, st); \
+    if (e != hipSuccess) return e;                                                               \
+    return launch_fwd<DD, CC, kFixedNorm, true, true>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, st); \
+  }
+    CASE2(64, false) CASE2(64, true) CASE2(128, false) CASE2(128, true)
+#undef CASE2
+    return hipErrorInvalidValue;
+  }
 #define CASE(DD, CC, VV)                                                                      \
   if (d == DD && (causal != 0) == CC && variant == VV) {                                       \
     if (extras) return launch_fwd<DD, CC, VV, true, true>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, st); \

@@ -69,11 +69,12 @@ def test_delta_bias_and_its_two_remedies(lib):
     std = lib.attn_fwd_opt(x["Q"], x["K"], x["V"], w.causal, w.alpha, 0, want_O_hp=True)
     mit = lib.attn_fwd_opt(x["Q"], x["K"], x["V"], w.causal, w.alpha, 1)
     single = lib.attn_fwd_opt(x["Q"], x["K"], x["V"], w.causal, w.alpha, 0, single_rounding=True)
+    row = lib.attn_fwd_opt(x["Q"], x["K"], x["V"], w.causal, w.alpha, 2)
     d_lp = lib.attn_delta(std["O"], x["dO"])
     d_hp = lib.attn_delta_hp(std["O_hp"], x["dO"])
     d_mit = lib.attn_delta(mit["O"], x["dO"])
     torch.cuda.synchronize()
-    e = {k: [] for k in ("lp", "hp", "mit", "O_std", "O_single")}
+    e = {k: [] for k in ("lp", "hp", "mit", "O_std", "O_single", "O_row")}
     for b in range(w.B):
         for h in range(w.H):
             xs = head_np(x, b, h)
@@ -83,6 +84,7 @@ def test_delta_bias_and_its_two_remedies(lib):
             e["mit"].append(_np(d_mit[b, h]) - d64)
             e["O_std"].append((_np(std["O"][b, h]) - O64).ravel())
             e["O_single"].append((_np(single["O"][b, h]) - O64).ravel())
+            e["O_row"].append((_np(row["O"][b, h]) - O64).ravel())
     m = {k: float(np.concatenate(v).mean()) for k, v in e.items()}
     print("mean signed errors on pairs_skew:", {k: f"{v:+.3e}" for k, v in m.items()})
     assert m["lp"] > 0
@@ -93,6 +95,7 @@ def test_delta_bias_and_its_two_remedies(lib):
     # rounding.  The emulation's sequential float32 sum leaves a residue of ~1/11 of the standard
     # bias; the matrix cores' own accumulation order leaves ~1/5 (measured +4.2e-4 vs -2.2e-3).
     assert m["O_std"] < 0 and abs(m["O_single"]) < abs(m["O_std"]) / 4
+    assert abs(m["O_row"]) < abs(m["O_std"]) / 10          # whole-row form of Alg. 3
 
 
 @pytest.mark.parametrize("variant", [0, 1])
@@ -214,3 +217,50 @@ def test_backward_from_each_delta(lib):
             got = _np(grads[k][name][b, h])
             assert metrics.rel_l2(got, rr) <= TOL_REL, (k, name)
             assert metrics.max_abs(got, rr) <= 1.25 * TOL_ABS, (k, name)
+
+
+@pytest.mark.parametrize("name,heads", [("tiny", [(0, 0)]), ("gpt2s", [(0, 0), (7, 11)]), ("tied_any", [(0, 0), (3, 5)]),
+                                        ("pairs_skew", [(2, 2)])])
+def test_whole_row_detection_variant(lib, name, heads):
+    """ATTN_VARIANT_MITIGATED_ROW against Alg. 3 applied to the whole row (the oracle with the key
+    tile equal to N): outputs within tolerance of fp64, per-row firing flags and unit-probability
+    counts equal to the oracle's, and the result independent of where the tied keys sit."""
+    w = synth.WORKLOADS[name]
+    x = synth.make(w, DEV)
+    r = lib.attn_fwd_opt(x["Q"], x["K"], x["V"], w.causal, w.alpha, 2, want_counts=True, want_O_hp=True)
+    plain = lib.attn_fwd(x["Q"], x["K"], x["V"], w.causal, w.alpha, 2)
+    torch.cuda.synchronize()
+    assert torch.equal(plain[0], r["O"]) and torch.equal(plain[1], r["LSE"])
+    for (b, h) in heads:
+        xs = head_np(x, b, h)
+        O64, L64 = exact.forward(xs["Q"], xs["K"], xs["V"], w.alpha, w.causal)
+        f = flash.forward(xs["Q"], xs["K"], xs["V"], w.alpha, w.causal, flash.MITIGATED, Bc=None)
+        got = _np(r["O"][b, h])
+        assert np.isfinite(got).all()
+        assert metrics.max_abs(got, O64) <= TOL_ABS and metrics.rel_l2(got, O64) <= TOL_REL
+        assert np.abs(_np(r["LSE"][b, h]) - L64).max() < 5e-3
+        assert metrics.rel_l2(_np(r["O_hp"][b, h]), f["Ohp"]) <= 1e-3
+        fired = r["fired"][b, h].cpu().numpy(); ones = r["ones"][b, h].cpu().numpy()
+        assert np.mean(fired != f["fired"]) <= 0.01 and np.mean(ones != f["ones"]) <= 0.01
+        print(f"{name} head {(b, h)}: rows where the whole-row rule fired {int(fired.sum())} (oracle {int(f['fired'].sum())})")
+
+
+def test_whole_row_detection_sees_ties_that_straddle_tiles(lib):
+    """Two bit-identical maximal keys placed in different 64-key tiles: the per-tile rule (Alg. 3
+    as written) does not see the repetition, the whole-row rule does."""
+    B, H, N, d = 1, 1, 256, 64
+    g = torch.Generator().manual_seed(77)
+    K = (0.3 * torch.randn((B, H, N, d), generator=g)).to(torch.bfloat16)
+    K[0, 0, 200] = K[0, 0, 10]                       # tiles 0 and 3
+    Q = (4.0 * K[:, :, 10:11].float()).expand(B, H, N, d).contiguous().to(torch.bfloat16)   # every query points at that key
+    V = torch.randn((B, H, N, d), generator=g).to(torch.bfloat16)
+    Q, K, V = Q.to(DEV), K.to(DEV), V.to(DEV)
+    tile = lib.attn_fwd_opt(Q, K, V, False, 0.125, 1, want_counts=True)
+    row = lib.attn_fwd_opt(Q, K, V, False, 0.125, 2, want_counts=True)
+    torch.cuda.synchronize()
+    assert int(tile["fired"].sum()) == 0 and (tile["ones"] == 2).all()
+    assert (row["fired"] == 1).all() and (row["ones"] == 0).all()
+    xs = {n: v[0, 0].double().cpu().numpy() for n, v in (("Q", Q), ("K", K), ("V", V))}
+    O64, _ = exact.forward(xs["Q"], xs["K"], xs["V"], 0.125, False)
+    for got in (tile, row):
+        assert metrics.max_abs(_np(got["O"][0, 0]), O64) <= TOL_ABS

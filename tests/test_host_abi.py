@@ -57,7 +57,7 @@ def test_argument_validation_happens_on_the_host(binding):
     assert fwd(p, p, p, p, p, 1, 1, 128, 96) == UNSUP        # head dim
     assert fwd(p, p, p, p, p, 1, 1, 0, 64) == UNSUP
     assert fwd(p, p, p, p, p, -1, 1, 128, 64) == BAD
-    assert fwd(p, p, p, p, p, 1, 1, 128, 64, var=2) == BAD
+    assert fwd(p, p, p, p, p, 1, 1, 128, 64, var=3) == BAD and fwd(p, p, p, p, p, 1, 1, 128, 64, var=-1) == BAD
     assert fwd(p, p, p, p, p, 1, 1, 128, 64, scale=0.0) == BAD
     assert fwd(None, p, p, p, p, 1, 1, 128, 64) == NULL
     assert fwd(p, p, p, p, None, 1, 1, 128, 64) == NULL
