@@ -65,38 +65,51 @@ def main():
     w = synth.WORKLOADS[args.workload]
     variant = {"standard": binding.STANDARD, "mitigated": binding.MITIGATED,
                "mitigated_row": binding.MITIGATED_ROW}[args.variant]
-    x = synth.make(w, dev)
-    B, H, N, d = w.B, w.H, w.N, w.d
-    O = torch.empty_like(x["Q"]); dQ = torch.empty_like(O); dK = torch.empty_like(O); dV = torch.empty_like(O)
-    L = torch.empty((B, H, N), dtype=torch.float32, device=dev)
-    delta = torch.empty((B, H, N), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
 
-    def step(var, ev=None):
-        if ev: ev[0].record(stream)
-        binding.attn_fwd(x["Q"], x["K"], x["V"], w.causal, w.alpha, var, O=O, LSE=L, stream=stream)
-        if ev: ev[1].record(stream)
-        binding.attn_delta(O, x["dO"], delta, stream=stream)
-        if ev: ev[2].record(stream)
-        binding.attn_bwd_dkdv(x["Q"], x["K"], x["V"], x["dO"], L, delta, w.causal, w.alpha, dK=dK, dV=dV, stream=stream)
-        if ev: ev[3].record(stream)
-        binding.attn_bwd_dq(x["Q"], x["K"], x["V"], x["dO"], L, delta, w.causal, w.alpha, dQ=dQ, stream=stream)
-        if ev: ev[4].record(stream)
+    class Job:
+        """One workload resident in HBM with its output buffers; step() = one pass of the hot path."""
+        def __init__(self, w):
+            self.w = w
+            self.x = synth.make(w, dev)
+            self.O = torch.empty_like(self.x["Q"])
+            self.dQ = torch.empty_like(self.O); self.dK = torch.empty_like(self.O); self.dV = torch.empty_like(self.O)
+            self.L = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device=dev)
+            self.delta = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device=dev)
 
-    def timed(var, steps, warmup):
-        for _ in range(warmup):
-            step(var)
-        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(steps):
-            step(var, evs[i])
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        names = ["fwd", "delta", "bwd_dkdv", "bwd_dq"]
-        per = {n: float(np.mean([evs[i][k].elapsed_time(evs[i][k + 1]) for i in range(steps)]))
-               for k, n in enumerate(names)}
-        return (t1 - t0) * 1e3 / steps, per
+        def step(self, var, ev=None):
+            w, x = self.w, self.x
+            if ev: ev[0].record(stream)
+            binding.attn_fwd(x["Q"], x["K"], x["V"], w.causal, w.alpha, var, O=self.O, LSE=self.L, stream=stream)
+            if ev: ev[1].record(stream)
+            binding.attn_delta(self.O, x["dO"], self.delta, stream=stream)
+            if ev: ev[2].record(stream)
+            binding.attn_bwd_dkdv(x["Q"], x["K"], x["V"], x["dO"], self.L, self.delta, w.causal, w.alpha,
+                                  dK=self.dK, dV=self.dV, stream=stream)
+            if ev: ev[3].record(stream)
+            binding.attn_bwd_dq(x["Q"], x["K"], x["V"], x["dO"], self.L, self.delta, w.causal, w.alpha,
+                                dQ=self.dQ, stream=stream)
+            if ev: ev[4].record(stream)
+
+        def timed(self, var, steps, warmup):
+            for _ in range(warmup):
+                self.step(var)
+            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(steps):
+                self.step(var, evs[i])
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            names = ["fwd", "delta", "bwd_dkdv", "bwd_dq"]
+            per = {n: float(np.mean([evs[i][k].elapsed_time(evs[i][k + 1]) for i in range(steps)]))
+                   for k, n in enumerate(names)}
+            return (t1 - t0) * 1e3 / steps, per
+
+    job = Job(w)
+    x = job.x
+    B, H, N, d = w.B, w.H, w.N, w.d
+    timed = job.timed
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -141,6 +154,21 @@ def main():
                      "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom))},
     }
+
+    # the other two throughput workloads of the build target, same step, fewer repetitions
+    also = {}
+    for name in ("gpt2s", "mid", "long"):
+        if name == w.name:
+            continue
+        j2 = Job(synth.WORKLOADS[name])
+        ms2, per2 = j2.timed(variant, max(5, args.steps // 2), 3)
+        f2 = j2.w.flops_fwd_bwd()
+        also[name] = {"value": round(f2 / (ms2 * 1e-3) / 1e12, 2), "ms_per_step": round(ms2, 4),
+                      "frac_of_bf16_peak": round(f2 / (ms2 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                      "kernel_ms": {k: round(v, 4) for k, v in per2.items()}}
+        del j2
+        torch.cuda.empty_cache()
+    out["other_workloads"] = also
 
     if not args.no_cpu_baseline:
         from oracle import exact

@@ -44,7 +44,7 @@ DEVI void store_acc_T(bf16_t* dst_row, const f32x16 (&acc)[D / 32], float scale,
 }
 
 template <int D, bool CAUSAL, bool RAGGED>
-__global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(
+__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, int N, float alpha) {
