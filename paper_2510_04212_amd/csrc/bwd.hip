@@ -64,7 +64,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
   const int nkt = (N + kKeysPerWG - 1) / kKeysPerWG;   // N need not be a multiple of the block
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nkt;
-  const int kt = wg % nkt;                         // early key blocks see the most queries: heavy first
+  // early key blocks see the most queries: heavy first
+  const int kt = (wg % nkt + (CAUSAL ? small_grid_rotation(bh, nkt, gridDim.x, D == 128 ? 384 : 768) : 0)) % nkt;
   const int k0 = kt * kKeysPerWG;
   const int kw = k0 + 32 * wave;
   const size_t head_off = (size_t)bh * N * D;
@@ -322,7 +323,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
   const int nqt = (N + kQPerWG - 1) / kQPerWG;
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nqt;
-  const int qt = nqt - 1 - (wg % nqt);
+  const int qt = nqt - 1 - (wg % nqt + (CAUSAL ? small_grid_rotation(bh, nqt, gridDim.x, D == 128 ? 768 : 1152) : 0)) % nqt;
   const int q0 = qt * kQPerWG;
   const int qw = q0 + 32 * wave;
   const size_t head_off = (size_t)bh * N * D;

@@ -236,3 +236,17 @@ DEVI int xcd_remap(int id, int n) {
   if ((n & 7) != 0) return id;
   return (id & 7) * (n >> 3) + (id >> 3);
 }
+
+// Rotation of the causal block order of one head, for grids small enough to be resident all at
+// once or nearly so (at most `capacity` work-groups, which callers set to 1.5x what the chip
+// holds of that kernel: measured, the rotation wins up to one and a half rounds of work-groups;
+// from two rounds on, plain heavy-first order does better and is kept).  Blocks of one head differ in
+// work by up to nblk : 1.  Work-groups are handed to the CUs of an XCD round-robin, so with a
+// fixed heavy-to-light order the j-th work-group of a CU always lands on the same weight class;
+// rotating the order by a different amount for each "lap" over the XCD's 32 CUs gives every CU
+// a mix.  The rotation depends on the head only, so every block is still visited once.
+DEVI int small_grid_rotation(int bh, int nblk, int grid, int capacity) {
+  if (grid > capacity || (grid & 7) != 0) return 0;
+  const int first = (bh * nblk) % (grid >> 3);     // dispatch sequence number of the head's first block inside its XCD
+  return (3 * (first >> 5)) % nblk;
+}

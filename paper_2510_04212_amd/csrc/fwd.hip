@@ -56,7 +56,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
   const int nqt = (N + kBr - 1) / kBr;
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nqt;
-  const int qt = nqt - 1 - (wg % nqt);          // heavy (late) query blocks first under the causal mask
+  // heavy (late) query blocks first under the causal mask
+  const int qt = nqt - 1 - (wg % nqt + (CAUSAL ? small_grid_rotation(bh, nqt, gridDim.x, D == 128 ? 768 : 1536) : 0)) % nqt;
   const int q0 = qt * kBr;
   const int qw = q0 + 32 * wave;                 // first query row of this wave
   const int q = qw + r;
