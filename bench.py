@@ -27,10 +27,10 @@ PEAK_HBM_GBS = 8000.0
 # scaled by the same counter's reading for a 1 GiB device copy (see profiles/mid_hbm_traffic.txt).
 # Keyed by (workload, kernel); None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("mid", "fwd"): 542205443,
-    ("mid", "delta"): 270608090,
-    ("mid", "bwd_dkdv"): 810128010,
-    ("mid", "bwd_dq"): 689152677,
+    ("mid", "fwd"): 539845066,
+    ("mid", "delta"): 270608709,
+    ("mid", "bwd_dkdv"): 810424138,
+    ("mid", "bwd_dq"): 686150746,
 }
 
 
@@ -43,6 +43,8 @@ def main():
     ap.add_argument("--variant", default="mitigated", choices=["standard", "mitigated", "mitigated_row"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--only-headline", action="store_true",
+                    help="time the chosen workload only (for profiler runs: one kernel shape per kernel name)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain device-to-device copies of 1 GiB (a kernel of known HBM traffic, "
                          "used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -158,7 +160,7 @@ def main():
     # the other two throughput workloads of the build target, same step, fewer repetitions
     also = {}
     for name in ("gpt2s", "mid", "long"):
-        if name == w.name:
+        if name == w.name or args.only_headline:
             continue
         j2 = Job(synth.WORKLOADS[name])
         ms2, per2 = j2.timed(variant, max(5, args.steps // 2), 3)
