@@ -149,83 +149,83 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
             top1 = fmaxf(top1, s[kb][i]);
           }
       } else {
-      float corr = 1.f;
-      float mneg;
-      if (VARIANT == kFixedNorm) {
-        mneg = -m * kLog2e;
-      } else {
-      // ---- tile row maximum r_m (of the alpha-scaled scores)
-      float mx = s[0][0];
+        float corr = 1.f;    // factor the accumulated output and row sum are multiplied by
+        float mneg;          // -m log2(e) of the normaliser used for this tile
+        if (VARIANT == kFixedNorm) {
+          mneg = -m * kLog2e;
+        } else {
+          // ---- tile row maximum r_m (of the alpha-scaled scores)
+          float mx = s[0][0];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+          for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
-      mx = max_with_partner32(mx);
-      const float r_m = mx * alpha;
-      float m_prime = r_m;
-      if (VARIANT == 1) {
-        // Alg. 3: r_s = #{ r_m - S <= eps } over the tile row; a repeated maximum moves the
-        // normaliser to beta*r_m (r_m > 0) or to 0 (r_m < 0).
-        // The count only matters through "more than one".  Each comparison yields a 64-lane
-        // mask in scalar registers; "seen once" / "seen twice" masks are then maintained with
-        // scalar instructions (one vector instruction per element instead of three), and the two
-        // lanes that share a query row are merged at the end.
-        const float thr = (r_m - eps) * inv_alpha;
-        unsigned long long once = 0ull, twice = 0ull;
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
+          mx = max_with_partner32(mx);
+          const float r_m = mx * alpha;
+          float m_prime = r_m;
+          if (VARIANT == 1) {
+            // Alg. 3: r_s = #{ r_m - S <= eps } over the tile row; a repeated maximum moves the
+            // normaliser to beta*r_m (r_m > 0) or to 0 (r_m < 0).
+            // The count only matters through "more than one".  Each comparison yields a 64-lane
+            // mask in scalar registers; "seen once" / "seen twice" masks are then maintained with
+            // scalar instructions (one vector instruction per element instead of three), and the
+            // two lanes that share a query row are merged at the end.
+            const float thr = (r_m - eps) * inv_alpha;
+            unsigned long long once = 0ull, twice = 0ull;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+              for (int i = 0; i < 16; ++i) {
+                const unsigned long long hit = __builtin_amdgcn_ballot_w64(s[kb][i] >= thr);
+                twice |= once & hit;
+                once |= hit;
+              }
+            const unsigned long long once_sw = (once >> 32) | (once << 32);
+            const unsigned long long twice_sw = (twice >> 32) | (twice << 32);
+            const unsigned long long rep = twice | twice_sw | (once & once_sw);
+            const bool repeated = ((rep >> lane) & 1ull) != 0ull;
+            m_prime = (repeated && r_m > 0.f) ? beta * r_m : r_m;
+            m_prime = (repeated && r_m < 0.f) ? 0.f : m_prime;
+            if (EXTRAS) fired_cnt += (m_prime != r_m) ? 1 : 0;
+          }
+          const float m_new = fmaxf(m, m_prime);         // Alg. 1 step 7 / Alg. 3
+          corr = __builtin_amdgcn_exp2f((m - m_new) * kLog2e);
+          m = m_new;
+          mneg = -m_new * kLog2e;
+        }
+        // ---- P-bar = exp(S - m), rounded to bf16; row sum of the ROUNDED values
+        bf16x8 pf[2][2];
+        float psum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const unsigned long long hit = __builtin_amdgcn_ballot_w64(s[kb][i] >= thr);
-            twice |= once & hit;
-            once |= hit;
-          }
-        const unsigned long long once_sw = (once >> 32) | (once << 32);
-        const unsigned long long twice_sw = (twice >> 32) | (twice << 32);
-        const unsigned long long rep = twice | twice_sw | (once & once_sw);
-        const bool repeated = ((rep >> lane) & 1ull) != 0ull;
-        m_prime = (repeated && r_m > 0.f) ? beta * r_m : r_m;
-        m_prime = (repeated && r_m < 0.f) ? 0.f : m_prime;
-        if (EXTRAS) fired_cnt += (m_prime != r_m) ? 1 : 0;
-      }
-      const float m_new = fmaxf(m, m_prime);         // Alg. 1 step 7 / Alg. 3
-      corr = __builtin_amdgcn_exp2f((m - m_new) * kLog2e);
-      m = m_new;
-      mneg = -m_new * kLog2e;
-      }
-      // ---- P-bar = exp(S - m), rounded to bf16; row sum of the ROUNDED values
-      bf16x8 pf[2][2];
-      float psum = 0.f;
+          for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+            for (int jj = 0; jj < 8; jj += 2) {
+              bf16x2 pp;
 #pragma unroll
-        for (int cc = 0; cc < 2; ++cc)
-#pragma unroll
-          for (int jj = 0; jj < 8; jj += 2) {
-            bf16x2 pp;
-#pragma unroll
-            for (int e = 0; e < 2; ++e)
-              pp[e] = (bf16_t)__builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][8 * cc + jj + e], c2, mneg));
-            pf[kb][cc][jj] = pp[0];
-            pf[kb][cc][jj + 1] = pp[1];
-            psum = add_pair_bf16(pp, psum);
-            if (EXTRAS) ones_cnt += ((float)pp[0] == 1.0f ? 1 : 0) + ((float)pp[1] == 1.0f ? 1 : 0);
-          }
-      lsum = lsum * corr + psum;
-      // ---- O^T <- diag(corr) O^T + V_j^T P-bar^T (Alg. 1 step 8)
-      if (VARIANT != kFixedNorm && __builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) acc[db][i] *= corr;
-      }
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int cc = 0; cc < 2; ++cc)
+              for (int e = 0; e < 2; ++e)
+                pp[e] = (bf16_t)__builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][8 * cc + jj + e], c2, mneg));
+              pf[kb][cc][jj] = pp[0];
+              pf[kb][cc][jj + 1] = pp[1];
+              psum = add_pair_bf16(pp, psum);
+              if (EXTRAS) ones_cnt += ((float)pp[0] == 1.0f ? 1 : 0) + ((float)pp[1] == 1.0f ? 1 : 0);
+            }
+        lsum = lsum * corr + psum;
+        // ---- O^T <- diag(corr) O^T + V_j^T P-bar^T (Alg. 1 step 8)
+        if (VARIANT != kFixedNorm && __builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {
 #pragma unroll
           for (int db = 0; db < D / 32; ++db)
-            acc[db] = mfma32(lds_col8<D>(tV, fo, 32 * kb + 16 * cc, db), pf[kb][cc], acc[db]);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[db][i] *= corr;
+        }
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+              acc[db] = mfma32(lds_col8<D>(tV, fo, 32 * kb + 16 * cc, db), pf[kb][cc], acc[db]);
       }
     }
     wait_vmem();

@@ -97,3 +97,28 @@ def test_argument_validation_happens_on_the_host(binding):
     assert bwd(alias, ws, 4096) == BAD                       # dK aliases dV
     nul = list(ptrs); nul[5] = None
     assert bwd(nul, ws, 4096) == NULL
+
+
+def test_binding_refuses_to_import_without_the_built_library(tmp_path):
+    """No fallback: a copy of the binding that has no libattn_gfx950.so beside it must not import."""
+    import shutil
+    import subprocess
+    import sys
+    pkg = tmp_path / "attn_binding_copy"
+    pkg.mkdir()
+    shutil.copy(os.path.join(ROOT, "paper_2510_04212_amd", "binding.py"), pkg / "binding.py")
+    (pkg / "__init__.py").write_text("")
+    r = subprocess.run([sys.executable, "-c", "import attn_binding_copy.binding"], cwd=tmp_path,
+                       capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "ImportError" in r.stderr and "libattn_gfx950.so" in r.stderr and "no CPU" in r.stderr
+
+
+def test_product_package_never_imports_the_oracle():
+    """The oracle is test infrastructure: nothing under the package may import it."""
+    pkg = os.path.join(ROOT, "paper_2510_04212_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith(".py"):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", text, flags=re.M), f
