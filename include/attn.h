@@ -180,6 +180,29 @@ int attn_bwd_dq(const void* Q, const void* K, const void* V, const void* dO, con
                 const float* delta, void* dQ,
                 int B, int H, int N, int d, int causal, float softmax_scale, void* stream);
 
+/*
+ * Strided forms of attn_fwd_ex and attn_bwd: element (b, h, n, k) of every bf16 tensor of the
+ * call (Q, K, V, O, dO, dQ, dK, dV) lives at  base + b*stride_b + h*stride_h + n*stride_n + k
+ * (strides in elements, the last dimension contiguous, the same three strides for all tensors
+ * of the call).  [B,H,N,d] contiguous is (H*N*d, N*d, d) and is what the other entry points use;
+ * [B,N,H,d] contiguous is (N*H*d, d, H*d); views into a fused projection buffer work as well.
+ * LSE and the workspace's delta stay float32 [B,H,N] contiguous.
+ * Strides must be positive multiples of 8 (every row starts on a 16-byte boundary) with
+ * d <= stride_n < 2^24, otherwise ATTN_ERR_BAD_ARG; that the strides describe non-overlapping
+ * memory inside the caller's allocations is the caller's responsibility.  Same arithmetic as
+ * the contiguous entry points: for equal values the results are bit-identical.
+ */
+int attn_fwd_strided(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                     long long stride_b, long long stride_h, long long stride_n,
+                     int B, int H, int N, int d, int causal, float softmax_scale, int variant,
+                     float beta, float eps, void* stream);
+int attn_bwd_strided(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                     const float* LSE, void* dQ, void* dK, void* dV,
+                     void* workspace, size_t workspace_bytes,
+                     long long stride_b, long long stride_h, long long stride_n,
+                     int B, int H, int N, int d, int causal, float softmax_scale, int variant,
+                     void* stream);
+
 /* Human-readable name of an attn_status (static storage, never NULL). */
 const char* attn_status_string(int status);
 

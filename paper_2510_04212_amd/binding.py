@@ -38,6 +38,11 @@ _lib.attn_delta_hp.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp]
 _lib.attn_delta_hp.restype = _i
 _lib.attn_delta_recompute.argtypes = [_vp] * 6 + [_i, _i, _i, _i, _i, _f, _vp]
 _lib.attn_delta_recompute.restype = _i
+_ll = ctypes.c_longlong
+_lib.attn_fwd_strided.argtypes = [_vp] * 5 + [_ll, _ll, _ll, _i, _i, _i, _i, _i, _f, _i, _f, _f, _vp]
+_lib.attn_fwd_strided.restype = _i
+_lib.attn_bwd_strided.argtypes = [_vp] * 9 + [_vp, _sz, _ll, _ll, _ll, _i, _i, _i, _i, _i, _f, _i, _vp]
+_lib.attn_bwd_strided.restype = _i
 _lib.attn_bwd.argtypes = [_vp] * 9 + [_vp, _sz, _i, _i, _i, _i, _i, _f, _i, _vp]
 _lib.attn_bwd.restype = _i
 _lib.attn_bwd_dkdv.argtypes = [_vp] * 8 + [_i, _i, _i, _i, _i, _f, _vp]
@@ -55,7 +60,7 @@ FWD_SINGLE_ROUNDING = 1
 
 EXPORTS = ["attn_fwd", "attn_fwd_ex", "attn_fwd_opt", "attn_delta", "attn_delta_hp",
            "attn_delta_recompute", "attn_bwd",
-           "attn_bwd_dkdv", "attn_bwd_dq",
+           "attn_bwd_dkdv", "attn_bwd_dq", "attn_fwd_strided", "attn_bwd_strided",
            "attn_bwd_workspace_bytes",
            "attn_status_string", "attn_fwd_key_tile"]
 
@@ -229,3 +234,53 @@ def attn_bwd_dq(Q, K, V, dO, LSE, delta, causal, softmax_scale, dQ=None, stream=
     _check(_lib.attn_bwd_dq(_ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(LSE), _ptr(delta), _ptr(dQ),
                             B, H, N, d, int(bool(causal)), float(softmax_scale), _stream(stream)))
     return dQ
+
+
+def _strided_bhnd(t, name, like=None):
+    """A CUDA bfloat16 tensor of logical shape [B,H,N,d] with a contiguous last dimension and any
+    batch / head / row strides (e.g. a permuted view of a [B,N,H,d] buffer)."""
+    if t.dtype != torch.bfloat16 or not t.is_cuda or t.dim() != 4 or t.stride(3) != 1:
+        raise ValueError(f"{name} must be a CUDA bfloat16 tensor [B,H,N,d] whose last dimension is contiguous")
+    if like is not None and (t.shape != like.shape or t.stride() != like.stride()):
+        raise ValueError(f"{name} must have the shape and strides of Q")
+    return t.shape, t.stride()
+
+
+def attn_fwd_strided(Q, K, V, causal, softmax_scale, variant=STANDARD, beta=None, eps=None,
+                     O=None, LSE=None, stream=None):
+    """attn_fwd_strided of the C ABI.  Q, K, V (and O, when given) share one set of strides;
+    O defaults to a tensor laid out like Q."""
+    (B, H, N, d), (sb, sh, sn, _) = _strided_bhnd(Q, "Q")
+    for n, t in (("K", K), ("V", V)):
+        _strided_bhnd(t, n, Q)
+    O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device) if O is None else O
+    _strided_bhnd(O, "O", Q)
+    if LSE is None:
+        LSE = torch.empty((B, H, N), dtype=torch.float32, device=Q.device)
+    _check(_lib.attn_fwd_strided(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), sb, sh, sn, B, H, N, d,
+                                 int(bool(causal)), float(softmax_scale), int(variant),
+                                 float(DEFAULT_BETA if beta is None else beta),
+                                 float(DEFAULT_EPS if eps is None else eps), _stream(stream)))
+    return O, LSE
+
+
+def attn_bwd_strided(Q, K, V, O, dO, LSE, causal, softmax_scale, variant=STANDARD,
+                     dQ=None, dK=None, dV=None, workspace=None, stream=None):
+    """attn_bwd_strided of the C ABI; every bf16 tensor shares Q's strides."""
+    (B, H, N, d), (sb, sh, sn, _) = _strided_bhnd(Q, "Q")
+    for n, t in (("K", K), ("V", V), ("O", O), ("dO", dO)):
+        _strided_bhnd(t, n, Q)
+    new = lambda: torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    dQ = new() if dQ is None else dQ
+    dK = new() if dK is None else dK
+    dV = new() if dV is None else dV
+    for n, t in (("dQ", dQ), ("dK", dK), ("dV", dV)):
+        _strided_bhnd(t, n, Q)
+    need = bwd_workspace_bytes(B, H, N, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Q.device)
+    _check(_lib.attn_bwd_strided(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ),
+                                 _ptr(dK), _ptr(dV), _ptr(workspace), workspace.numel(), sb, sh, sn,
+                                 B, H, N, d, int(bool(causal)), float(softmax_scale), int(variant),
+                                 _stream(stream)))
+    return dQ, dK, dV

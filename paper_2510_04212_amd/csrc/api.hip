@@ -4,21 +4,45 @@
 #include <cmath>
 #include "../../include/attn.h"
 
+// Mirrors the device-side struct of the same name (common.hpp): element (b,h,n,k) of a bf16
+// tensor lives at b*sb + h*sh + n*sn + k.
+struct Layout {
+  long long sb, sh;
+  int sn;
+  int H;
+};
+
 hipError_t attn_fwd_dispatch(const void*, const void*, const void*, void*, float*, int, int, int,
-                             int, float, int, float, float, float*, int*, int*, int, hipStream_t);
-hipError_t attn_delta_dispatch(const void*, const void*, float*, long, int, int, hipStream_t);
+                             int, float, int, float, float, float*, int*, int*, int, Layout,
+                             hipStream_t);
+hipError_t attn_delta_dispatch(const void*, const void*, float*, long, int, int, int, Layout,
+                               hipStream_t);
 hipError_t attn_bwd_dkdv_dispatch(const void*, const void*, const void*, const void*, const float*,
-                                  const float*, void*, void*, int, int, int, int, float,
+                                  const float*, void*, void*, int, int, int, int, float, Layout,
                                   hipStream_t);
 hipError_t attn_bwd_dq_dispatch(const void*, const void*, const void*, const void*, const float*,
-                                const float*, void*, int, int, int, int, float, hipStream_t);
+                                const float*, void*, int, int, int, int, float, Layout,
+                                hipStream_t);
 hipError_t attn_delta_recompute_dispatch(const void*, const void*, const void*, const void*,
-                                         const float*, float*, int, int, int, int, float,
+                                         const float*, float*, int, int, int, int, float, Layout,
                                          hipStream_t);
 
 namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+Layout contiguous(int H, int N, int d) {
+  return Layout{(long long)H * N * d, (long long)N * d, d, H};
+}
+
+// Strides of the strided entry points: positive multiples of 8 elements (rows start on 16-byte
+// boundaries), rows at least d apart, and small enough for the 32-bit per-lane offsets the tile
+// loader uses inside a 64-row tile.
+bool strides_ok(long long sb, long long sh, long long sn, int d) {
+  if (sb <= 0 || sh <= 0 || sn <= 0) return false;
+  if ((sb & 7) || (sh & 7) || (sn & 7)) return false;
+  return sn >= d && sn < (1ll << 24);
+}
 
 // Shape check shared by all entry points.  Returns ATTN_OK with *empty = true for B*H == 0.
 int check_shape(int B, int H, int N, int d, bool* empty) {
@@ -47,10 +71,11 @@ extern "C" const char* attn_status_string(int status) {
   }
 }
 
-extern "C" int attn_fwd_opt(const void* Q, const void* K, const void* V, void* O, float* LSE,
-                            float* O_hp, int* ones_count, int* fired_count,
-                            int B, int H, int N, int d, int causal, float softmax_scale,
-                            int variant, float beta, float eps, unsigned flags, void* stream) {
+static int fwd_entry(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                     float* O_hp, int* ones_count, int* fired_count,
+                     int B, int H, int N, int d, int causal, float softmax_scale,
+                     int variant, float beta, float eps, unsigned flags, const Layout* user_lay,
+                     void* stream) {
   bool empty;
   if (flags & ~(unsigned)ATTN_FWD_SINGLE_ROUNDING) return ATTN_ERR_BAD_ARG;
   int st = check_shape(B, H, N, d, &empty);
@@ -69,11 +94,31 @@ extern "C" int attn_fwd_opt(const void* Q, const void* K, const void* V, void* O
   if (!aligned16(O_hp) || !aligned16(ones_count) || !aligned16(fired_count)) return ATTN_ERR_BAD_ARG;
   if (O_hp && (O_hp == Q || O_hp == K || O_hp == V || O_hp == O)) return ATTN_ERR_BAD_ARG;
   if (ones_count && ones_count == fired_count) return ATTN_ERR_BAD_ARG;
+  const Layout lay = user_lay ? *user_lay : contiguous(H, N, d);
   hipError_t e = attn_fwd_dispatch(Q, K, V, O, LSE, B * H, N, d, causal, softmax_scale, variant,
                                    beta, eps, O_hp, ones_count, fired_count,
-                                   (flags & ATTN_FWD_SINGLE_ROUNDING) ? 1 : 0,
+                                   (flags & ATTN_FWD_SINGLE_ROUNDING) ? 1 : 0, lay,
                                    static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+extern "C" int attn_fwd_opt(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                            float* O_hp, int* ones_count, int* fired_count,
+                            int B, int H, int N, int d, int causal, float softmax_scale,
+                            int variant, float beta, float eps, unsigned flags, void* stream) {
+  return fwd_entry(Q, K, V, O, LSE, O_hp, ones_count, fired_count, B, H, N, d, causal,
+                   softmax_scale, variant, beta, eps, flags, nullptr, stream);
+}
+
+extern "C" int attn_fwd_strided(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                                long long stride_b, long long stride_h, long long stride_n,
+                                int B, int H, int N, int d, int causal, float softmax_scale,
+                                int variant, float beta, float eps, void* stream) {
+  if (B < 0 || H < 0 || N < 0 || d < 0) return ATTN_ERR_BAD_ARG;
+  if (!strides_ok(stride_b, stride_h, stride_n, d)) return ATTN_ERR_BAD_ARG;
+  const Layout lay{stride_b, stride_h, (int)stride_n, H};
+  return fwd_entry(Q, K, V, O, LSE, nullptr, nullptr, nullptr, B, H, N, d, causal, softmax_scale,
+                   variant, beta, eps, 0u, &lay, stream);
 }
 
 extern "C" int attn_fwd_ex(const void* Q, const void* K, const void* V, void* O, float* LSE,
@@ -99,8 +144,8 @@ static int delta_entry(const void* O, const void* dO, float* delta, int B, int H
   if (!O || !dO || !delta) return ATTN_ERR_NULL;
   if (!aligned16(O) || !aligned16(dO) || !aligned16(delta)) return ATTN_ERR_BAD_ARG;
   if (static_cast<const void*>(delta) == O || static_cast<const void*>(delta) == dO) return ATTN_ERR_BAD_ARG;
-  hipError_t e = attn_delta_dispatch(O, dO, delta, (long)B * H * N, d, o_is_f32,
-                                     static_cast<hipStream_t>(stream));
+  hipError_t e = attn_delta_dispatch(O, dO, delta, (long)B * H * N, N, d, o_is_f32,
+                                     contiguous(H, N, d), static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
@@ -145,7 +190,8 @@ extern "C" int attn_bwd_dkdv(const void* Q, const void* K, const void* V, const 
     if (p == dK || p == dV) return ATTN_ERR_BAD_ARG;
   if (dK == dV) return ATTN_ERR_BAD_ARG;
   hipError_t e = attn_bwd_dkdv_dispatch(Q, K, V, dO, LSE, delta, dK, dV, B * H, N, d, causal,
-                                        softmax_scale, static_cast<hipStream_t>(stream));
+                                        softmax_scale, contiguous(H, N, d),
+                                        static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
@@ -164,14 +210,15 @@ extern "C" int attn_bwd_dq(const void* Q, const void* K, const void* V, const vo
   for (const void* p : ins)
     if (p == dQ) return ATTN_ERR_BAD_ARG;
   hipError_t e = attn_bwd_dq_dispatch(Q, K, V, dO, LSE, delta, dQ, B * H, N, d, causal,
-                                      softmax_scale, static_cast<hipStream_t>(stream));
+                                      softmax_scale, contiguous(H, N, d),
+                                      static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
-extern "C" int attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
-                        const float* LSE, void* dQ, void* dK, void* dV, void* workspace,
-                        size_t workspace_bytes, int B, int H, int N, int d, int causal,
-                        float softmax_scale, int variant, void* stream) {
+static int bwd_entry(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                     const float* LSE, void* dQ, void* dK, void* dV, void* workspace,
+                     size_t workspace_bytes, int B, int H, int N, int d, int causal,
+                     float softmax_scale, int variant, const Layout* user_lay, void* stream) {
   bool empty;
   int st = check_shape(B, H, N, d, &empty);
   if (st != ATTN_OK) return st;
@@ -192,12 +239,34 @@ extern "C" int attn_bwd(const void* Q, const void* K, const void* V, const void*
     return ATTN_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   float* delta = static_cast<float*>(workspace);
-  hipError_t e = attn_delta_dispatch(O, dO, delta, (long)B * H * N, d, 0, s);
+  const Layout lay = user_lay ? *user_lay : contiguous(H, N, d);
+  hipError_t e = attn_delta_dispatch(O, dO, delta, (long)B * H * N, N, d, 0, lay, s);
   if (e != hipSuccess) return ATTN_ERR_LAUNCH;
-  e = attn_bwd_dkdv_dispatch(Q, K, V, dO, LSE, delta, dK, dV, B * H, N, d, causal, softmax_scale, s);
+  e = attn_bwd_dkdv_dispatch(Q, K, V, dO, LSE, delta, dK, dV, B * H, N, d, causal, softmax_scale, lay, s);
   if (e != hipSuccess) return ATTN_ERR_LAUNCH;
-  e = attn_bwd_dq_dispatch(Q, K, V, dO, LSE, delta, dQ, B * H, N, d, causal, softmax_scale, s);
+  e = attn_bwd_dq_dispatch(Q, K, V, dO, LSE, delta, dQ, B * H, N, d, causal, softmax_scale, lay, s);
   return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+extern "C" int attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                        const float* LSE, void* dQ, void* dK, void* dV, void* workspace,
+                        size_t workspace_bytes, int B, int H, int N, int d, int causal,
+                        float softmax_scale, int variant, void* stream) {
+  return bwd_entry(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, H, N, d, causal,
+                   softmax_scale, variant, nullptr, stream);
+}
+
+extern "C" int attn_bwd_strided(const void* Q, const void* K, const void* V, const void* O,
+                                const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
+                                void* workspace, size_t workspace_bytes,
+                                long long stride_b, long long stride_h, long long stride_n,
+                                int B, int H, int N, int d, int causal, float softmax_scale,
+                                int variant, void* stream) {
+  if (B < 0 || H < 0 || N < 0 || d < 0) return ATTN_ERR_BAD_ARG;
+  if (!strides_ok(stride_b, stride_h, stride_n, d)) return ATTN_ERR_BAD_ARG;
+  const Layout lay{stride_b, stride_h, (int)stride_n, H};
+  return bwd_entry(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, H, N, d, causal,
+                   softmax_scale, variant, &lay, stream);
 }
 
 extern "C" int attn_delta_recompute(const void* Q, const void* K, const void* V, const void* dO,
@@ -214,6 +283,7 @@ extern "C" int attn_delta_recompute(const void* Q, const void* K, const void* V,
   for (int i = 0; i < 5; ++i)
     if (ptrs[i] == static_cast<const void*>(delta)) return ATTN_ERR_BAD_ARG;
   hipError_t e = attn_delta_recompute_dispatch(Q, K, V, dO, LSE, delta, B * H, N, d, causal,
-                                               softmax_scale, static_cast<hipStream_t>(stream));
+                                               softmax_scale, contiguous(H, N, d),
+                                               static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
 }

@@ -47,7 +47,7 @@ template <int D, bool CAUSAL, bool RAGGED>
 __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
-    bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, int N, float alpha) {
+    bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, int N, float alpha, Layout lay) {
   constexpr int TILE_BYTES = kQTile * D * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   // layout: Q buffers [2][TILE_BYTES], dO buffers [2][TILE_BYTES], L2 [2][64] float, delta [2][64] float
@@ -68,7 +68,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
   const int kt = (wg % nkt + (CAUSAL ? small_grid_rotation(bh, nkt, gridDim.x, D == 128 ? 384 : 768) : 0)) % nkt;
   const int k0 = kt * kKeysPerWG;
   const int kw = k0 + 32 * wave;
-  const size_t head_off = (size_t)bh * N * D;
+  const size_t head_off = head_base(lay, bh);
+  const int sn = lay.sn;
   const bf16_t* Qh = Q + head_off;
   const bf16_t* dOh = dO + head_off;
   const float* Lh = LSE + (size_t)bh * N;
@@ -80,8 +81,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
   bf16x8 kf[D / 16], vf[D / 16];
 #pragma unroll
   for (int kc = 0; kc < D / 16; ++kc) {
-    kf[kc] = *reinterpret_cast<const bf16x8*>(K + head_off + (size_t)keyc * D + 16 * kc + 8 * h);
-    vf[kc] = *reinterpret_cast<const bf16x8*>(V + head_off + (size_t)keyc * D + 16 * kc + 8 * h);
+    kf[kc] = *reinterpret_cast<const bf16x8*>(K + head_off + (size_t)keyc * sn + 16 * kc + 8 * h);
+    vf[kc] = *reinterpret_cast<const bf16x8*>(V + head_off + (size_t)keyc * sn + 16 * kc + 8 * h);
   }
   f32x16 dVt[D / 32], dKt[D / 32];
 #pragma unroll
@@ -98,7 +99,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
   // from -delta, so that the matrix instructions deliver dP - delta directly (Alg. 2 step 12).
   float sreg = 0.f;
   TileLoader<D> loader;
-  loader.init(tid);
+  loader.init(tid, sn);
   FragOffsets<D> fo;
   init_frag_offsets<D>(fo, lane);
   auto load_tile = [&](int t, int buf) {
@@ -297,8 +298,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
     if (t + 1 < nt) tile_step(std::integral_constant<int, 1>{}, t + 1);
   }
   if (!RAGGED || kw + r < N) {
-    store_acc_T<D>(dV + head_off + (size_t)(kw + r) * D, dVt, 1.0f, h);
-    store_acc_T<D>(dK + head_off + (size_t)(kw + r) * D, dKt, alpha, h);
+    store_acc_T<D>(dV + head_off + (size_t)(kw + r) * sn, dVt, 1.0f, h);
+    store_acc_T<D>(dK + head_off + (size_t)(kw + r) * sn, dKt, alpha, h);
   }
 }
 
@@ -309,7 +310,7 @@ template <int D, bool CAUSAL, bool RAGGED, bool DELTA_MODE>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
-    bf16_t* __restrict__ dQ, float* __restrict__ delta_out, int N, float alpha) {
+    bf16_t* __restrict__ dQ, float* __restrict__ delta_out, int N, float alpha, Layout lay) {
   constexpr int TILE_BYTES = kKTile * D * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* ldsK = smem;
@@ -326,7 +327,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
   const int qt = nqt - 1 - (wg % nqt + (CAUSAL ? small_grid_rotation(bh, nqt, gridDim.x, D == 128 ? 768 : 1152) : 0)) % nqt;
   const int q0 = qt * kQPerWG;
   const int qw = q0 + 32 * wave;
-  const size_t head_off = (size_t)bh * N * D;
+  const size_t head_off = head_base(lay, bh);
+  const int sn = lay.sn;
   const bf16_t* Kh = K + head_off;
   const bf16_t* Vh = V + head_off;
 
@@ -336,8 +338,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
   bf16x8 qf[D / 16], dof[D / 16];
 #pragma unroll
   for (int kc = 0; kc < D / 16; ++kc) {
-    qf[kc] = *reinterpret_cast<const bf16x8*>(Q + head_off + (size_t)qc * D + 16 * kc + 8 * h);
-    dof[kc] = *reinterpret_cast<const bf16x8*>(dO + head_off + (size_t)qc * D + 16 * kc + 8 * h);
+    qf[kc] = *reinterpret_cast<const bf16x8*>(Q + head_off + (size_t)qc * sn + 16 * kc + 8 * h);
+    dof[kc] = *reinterpret_cast<const bf16x8*>(dO + head_off + (size_t)qc * sn + 16 * kc + 8 * h);
   }
   const float l2 = LSE[(size_t)bh * N + qc] * kLog2e;
   const float dl = DELTA_MODE ? 0.f : delta[(size_t)bh * N + qc];
@@ -360,7 +362,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
   const float c2 = alpha * kLog2e;
 
   TileLoader<D> loader;
-  loader.init(tid);
+  loader.init(tid, sn);
   loader.template load_rows<RAGGED>(ldsK, Kh, 0, N, tid);
   loader.template load_rows<RAGGED>(ldsV, Vh, 0, N, tid);
   wait_vmem();
@@ -436,7 +438,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     if (h == 0 && (!RAGGED || qw + r < N)) delta_out[(size_t)bh * N + qw + r] = dsum;
     return;
   }
-  if (!RAGGED || qw + r < N) store_acc_T<D>(dQ + head_off + (size_t)(qw + r) * D, dQt, alpha, h);
+  if (!RAGGED || qw + r < N) store_acc_T<D>(dQ + head_off + (size_t)(qw + r) * sn, dQt, alpha, h);
 }
 
 template <typename KernT>
@@ -451,7 +453,7 @@ static hipError_t set_smem(KernT kern, int smem, bool& done) {
 template <int D, bool CAUSAL, bool RAGGED>
 static hipError_t launch_dkdv(const void* Q, const void* K, const void* V, const void* dO,
                               const float* LSE, const float* delta, void* dK, void* dV, int BH,
-                              int N, float alpha, hipStream_t st) {
+                              int N, float alpha, Layout lay, hipStream_t st) {
   constexpr int smem = 4 * kQTile * D * 2 + 4 * kQTile * (int)sizeof(float);
   static bool set = false;
   auto k = attn_bwd_dkdv_kernel<D, CAUSAL, RAGGED>;
@@ -459,14 +461,14 @@ static hipError_t launch_dkdv(const void* Q, const void* K, const void* V, const
   if ((e = set_smem(k, smem, set)) != hipSuccess) return e;
   hipLaunchKernelGGL(k, dim3(BH * ((N + kKeysPerWG - 1) / kKeysPerWG)), dim3(256), smem, st, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
-                     (bf16_t*)dK, (bf16_t*)dV, N, alpha);
+                     (bf16_t*)dK, (bf16_t*)dV, N, alpha, lay);
   return hipGetLastError();
 }
 
 template <int D, bool CAUSAL, bool RAGGED, bool DELTA_MODE>
 static hipError_t launch_dq(const void* Q, const void* K, const void* V, const void* dO,
                             const float* LSE, const float* delta, void* dQ, float* delta_out,
-                            int BH, int N, float alpha, hipStream_t st) {
+                            int BH, int N, float alpha, Layout lay, hipStream_t st) {
   constexpr int smem = 4 * kKTile * D * 2;
   static bool set = false;
   auto k = attn_bwd_dq_kernel<D, CAUSAL, RAGGED, DELTA_MODE>;
@@ -474,7 +476,7 @@ static hipError_t launch_dq(const void* Q, const void* K, const void* V, const v
   if ((e = set_smem(k, smem, set)) != hipSuccess) return e;
   hipLaunchKernelGGL(k, dim3(BH * ((N + kQPerWG - 1) / kQPerWG)), dim3(256), smem, st, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
-                     (bf16_t*)dQ, delta_out, N, alpha);
+                     (bf16_t*)dQ, delta_out, N, alpha, lay);
   return hipGetLastError();
 }
 
@@ -482,11 +484,12 @@ static hipError_t launch_dq(const void* Q, const void* K, const void* V, const v
 
 hipError_t attn_bwd_dkdv_dispatch(const void* Q, const void* K, const void* V, const void* dO,
                                   const float* LSE, const float* delta, void* dK, void* dV,
-                                  int BH, int N, int d, int causal, float alpha, hipStream_t st) {
+                                  int BH, int N, int d, int causal, float alpha, Layout lay,
+                                  hipStream_t st) {
   const bool ragged = (N % kKeysPerWG) != 0;     // the aligned kernels carry no bounds handling
 #define CASE(DD, CC, RR)                                                \
   if (d == DD && (causal != 0) == CC && ragged == RR)                   \
-    return launch_dkdv<DD, CC, RR>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, st);
+    return launch_dkdv<DD, CC, RR>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, lay, st);
   CASE(64, false, false) CASE(64, false, true) CASE(64, true, false) CASE(64, true, true)
   CASE(128, false, false) CASE(128, false, true) CASE(128, true, false) CASE(128, true, true)
 #undef CASE
@@ -495,11 +498,11 @@ hipError_t attn_bwd_dkdv_dispatch(const void* Q, const void* K, const void* V, c
 
 hipError_t attn_bwd_dq_dispatch(const void* Q, const void* K, const void* V, const void* dO,
                                 const float* LSE, const float* delta, void* dQ, int BH, int N,
-                                int d, int causal, float alpha, hipStream_t st) {
+                                int d, int causal, float alpha, Layout lay, hipStream_t st) {
   const bool ragged = (N % kQPerWG) != 0;
 #define CASE(DD, CC, RR)                                                \
   if (d == DD && (causal != 0) == CC && ragged == RR)                   \
-    return launch_dq<DD, CC, RR, false>(Q, K, V, dO, LSE, delta, dQ, nullptr, BH, N, alpha, st);
+    return launch_dq<DD, CC, RR, false>(Q, K, V, dO, LSE, delta, dQ, nullptr, BH, N, alpha, lay, st);
   CASE(64, false, false) CASE(64, false, true) CASE(64, true, false) CASE(64, true, true)
   CASE(128, false, false) CASE(128, false, true) CASE(128, true, false) CASE(128, true, true)
 #undef CASE
@@ -510,10 +513,10 @@ hipError_t attn_bwd_dq_dispatch(const void* Q, const void* K, const void* V, con
 hipError_t attn_delta_recompute_dispatch(const void* Q, const void* K, const void* V,
                                          const void* dO, const float* LSE, float* delta_out,
                                          int BH, int N, int d, int causal, float alpha,
-                                         hipStream_t st) {
+                                         Layout lay, hipStream_t st) {
 #define CASE(DD, CC)                                  \
   if (d == DD && (causal != 0) == CC)                 \
-    return launch_dq<DD, CC, true, true>(Q, K, V, dO, LSE, nullptr, nullptr, delta_out, BH, N, alpha, st);
+    return launch_dq<DD, CC, true, true>(Q, K, V, dO, LSE, nullptr, nullptr, delta_out, BH, N, alpha, lay, st);
   CASE(64, false) CASE(64, true) CASE(128, false) CASE(128, true)
 #undef CASE
   return hipErrorInvalidValue;

@@ -130,6 +130,19 @@ DEVI float sum_with_partner32(float x) {
 
 DEVI float bf16_bits_to_float(unsigned short b) { return __uint_as_float(((unsigned)b) << 16); }
 
+// Addressing of the bf16 tensors Q, K, V, O, dO, dQ, dK, dV: element (b, h, n, k) lives at
+// b*sb + h*sh + n*sn + k (the last dimension is contiguous).  [B,H,N,d] contiguous is
+// (H*N*d, N*d, d); [B,N,H,d] is (N*H*d, d, H*d).  float32 per-row tensors (LSE, delta) and the
+// optional float32 / int32 outputs are always contiguous [B,H,N(,d)].
+struct Layout {
+  long long sb, sh;
+  int sn;
+  int H;
+};
+DEVI size_t head_base(const Layout& lay, int bh) {
+  return (size_t)(bh / lay.H) * (size_t)lay.sb + (size_t)(bh % lay.H) * (size_t)lay.sh;
+}
+
 // Asynchronous copy of a 64-row x D bf16 tile from global memory straight into swizzled LDS
 // (global_load_lds_dwordx4: no registers are involved; completion is tracked by vmcnt).
 // One wave-instruction moves 64 x 16 bytes to LDS base + 16*lane, i.e. 1024 consecutive bytes =
@@ -149,13 +162,15 @@ template <int D> struct TileLoader {
   static constexpr int NI = 64 / RPI / 4;        // instructions per wave (4 waves share a tile)
   unsigned voff[NI];                             // per-lane byte offset inside the source tile
   unsigned lds_wave;                             // byte offset of this wave's first row in the LDS tile
-  DEVI void init(int tid) {
+  int sn;                                        // distance between consecutive rows of the source, in elements
+  DEVI void init(int tid, int row_stride) {
     const int wave = tid >> 6, lane = tid & 63;
+    sn = row_stride;
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       const int row = (wave * NI + i) * RPI + lane / CH;
       const int c = (lane % CH) ^ swz<D>(row);
-      voff[i] = (unsigned)(row * D + c * 8) * 2u;
+      voff[i] = (unsigned)(row * sn + c * 8) * 2u;
     }
     lds_wave = (unsigned)(wave * NI * RPI * D * 2);
   }
@@ -171,7 +186,7 @@ template <int D> struct TileLoader {
       const int row = (wave * NI + i) * RPI + lane / CH;
       const int c = (lane % CH) ^ swz<D>(row);
       const int rc = row < valid ? row : valid - 1;
-      const unsigned vo = (unsigned)(rc * D + c * 8) * 2u;
+      const unsigned vo = (unsigned)(rc * sn + c * 8) * 2u;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                    :
                    : "s"(base + (unsigned)(i * RPI * D * 2)), "v"(vo), "s"(src)
@@ -182,7 +197,7 @@ template <int D> struct TileLoader {
   // reach past row N-1 and is then loaded clamped; otherwise every tile is known to be full.
   template <bool RAGGED>
   DEVI void load_rows(const char* tile, const bf16_t* tensor, int row0, int N, int tid) const {
-    const bf16_t* src = tensor + (size_t)row0 * D;
+    const bf16_t* src = tensor + (size_t)row0 * sn;
     if (!RAGGED || row0 + 64 <= N) load(tile, src);
     else load_clamped(tile, src, N - row0, tid);
   }

@@ -11,7 +11,8 @@ namespace {
 template <int D, int UNROLL, bool OHP>
 __global__ __launch_bounds__(256) void attn_delta_kernel(const void* __restrict__ Ov,
                                                          const bf16_t* __restrict__ dO,
-                                                         float* __restrict__ delta, long rows) {
+                                                         float* __restrict__ delta, long rows,
+                                                         int N, Layout lay) {
   const bf16_t* O = static_cast<const bf16_t*>(Ov);
   const float* Of = static_cast<const float*>(Ov);
   constexpr int LPR = D / 8;             // lanes per row
@@ -25,13 +26,15 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const void* __restrict_
   for (int u = 0; u < UNROLL; ++u) {
     long rr = row + (long)u * RPB;
     if (rr < rows) {
+      // row rr of the [B,H,N] order -> its place in the (possibly strided) bf16 tensors
+      const size_t at = head_base(lay, (int)(rr / N)) + (size_t)(rr % N) * lay.sn + sub * 8;
       if (OHP) {
         f0[u] = *reinterpret_cast<const f32x4*>(Of + rr * D + sub * 8);
         f1[u] = *reinterpret_cast<const f32x4*>(Of + rr * D + sub * 8 + 4);
       } else {
-        a[u] = *reinterpret_cast<const u32x4*>(O + rr * D + sub * 8);
+        a[u] = *reinterpret_cast<const u32x4*>(O + at);
       }
-      b[u] = *reinterpret_cast<const u32x4*>(dO + rr * D + sub * 8);
+      b[u] = *reinterpret_cast<const u32x4*>(dO + at);
     } else {
       a[u] = u32x4{0, 0, 0, 0};
       b[u] = u32x4{0, 0, 0, 0};
@@ -65,8 +68,8 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const void* __restrict_
 }  // namespace
 
 // o_is_f32: O points to float32 values (O_hp) instead of bf16.
-hipError_t attn_delta_dispatch(const void* O, const void* dO, float* delta, long rows, int d,
-                               int o_is_f32, hipStream_t st) {
+hipError_t attn_delta_dispatch(const void* O, const void* dO, float* delta, long rows, int N, int d,
+                               int o_is_f32, Layout lay, hipStream_t st) {
   constexpr int UNROLL = 4;
   if (rows == 0) return hipSuccess;
   if (d != 64 && d != 128) return hipErrorInvalidValue;
@@ -74,7 +77,7 @@ hipError_t attn_delta_dispatch(const void* O, const void* dO, float* delta, long
   dim3 grid((unsigned)((rows + rpb - 1) / rpb));
 #define LAUNCH(DD, HP)                                                                          \
   hipLaunchKernelGGL((attn_delta_kernel<DD, UNROLL, HP>), grid, dim3(256), 0, st, O,           \
-                     (const bf16_t*)dO, delta, rows)
+                     (const bf16_t*)dO, delta, rows, N, lay)
   if (d == 128) { if (o_is_f32) LAUNCH(128, true); else LAUNCH(128, false); }
   else          { if (o_is_f32) LAUNCH(64, true); else LAUNCH(64, false); }
 #undef LAUNCH

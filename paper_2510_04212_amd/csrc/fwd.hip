@@ -41,7 +41,7 @@ template <int D, bool CAUSAL, int VARIANT, bool RAGGED, bool EXTRAS>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, float* __restrict__ LSE, int N, float alpha, float beta, float eps,
-    FwdExtras ex) {
+    FwdExtras ex, Layout lay) {
   constexpr int TILE_BYTES = kBc * D * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   // layout: K buffers [2][TILE_BYTES], then V buffers [2][TILE_BYTES]
@@ -62,13 +62,14 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
   const int qw = q0 + 32 * wave;                 // first query row of this wave
   const int q = qw + r;
   const int qc = (RAGGED && q >= N) ? N - 1 : q;   // row actually read for this lane
-  const size_t head_off = (size_t)bh * N * D;
+  const size_t head_off = head_base(lay, bh);
+  const int sn = lay.sn;
   const bf16_t* Qh = Q + head_off;
   const bf16_t* Kh = K + head_off;
   const bf16_t* Vh = V + head_off;
 
   TileLoader<D> loader;
-  loader.init(tid);
+  loader.init(tid, sn);
   FragOffsets<D> fo;
   init_frag_offsets<D>(fo, lane);
 
@@ -81,7 +82,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
   bf16x8 qf[D / 16];
 #pragma unroll
   for (int kc = 0; kc < D / 16; ++kc)
-    qf[kc] = *reinterpret_cast<const bf16x8*>(Qh + (size_t)qc * D + 16 * kc + 8 * h);
+    qf[kc] = *reinterpret_cast<const bf16x8*>(Qh + (size_t)qc * sn + 16 * kc + 8 * h);
 
   f32x16 acc[D / 32];
 #pragma unroll
@@ -261,7 +262,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
     ones_row = (int)(sw[0] + sw[1]);
   }
   if (RAGGED && q >= N) return;                            // rows past the sequence end exist only as padding
-  bf16_t* Oq = O + head_off + (size_t)q * D;
+  bf16_t* Oq = O + head_off + (size_t)q * sn;
   const bool keep_obar_f32 = EXTRAS && ex.single_rounding != 0;
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
@@ -279,7 +280,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
         f32x4 hp;
 #pragma unroll
         for (int e = 0; e < 4; ++e) hp[e] = acc[db][4 * g + e] / l;
-        *reinterpret_cast<f32x4*>(ex.O_hp + head_off + (size_t)q * D + 32 * db + 8 * g + 4 * h) = hp;
+        *reinterpret_cast<f32x4*>(ex.O_hp + ((size_t)bh * N + q) * D + 32 * db + 8 * g + 4 * h) = hp;
       }
     }
   if (h == 0) {
@@ -296,7 +297,7 @@ extern "C" int attn_fwd_key_tile(int d) { return (d == 64 || d == 128) ? kBc : 0
 template <int D, bool CAUSAL, int VARIANT, bool RAGGED, bool EXTRAS>
 static hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
                              int BH, int N, float alpha, float beta, float eps, FwdExtras ex,
-                             hipStream_t st) {
+                             Layout lay, hipStream_t st) {
   constexpr int smem = 4 * kBc * D * 2;
   static bool attr_set = false;
   auto kern = attn_fwd_kernel<D, CAUSAL, VARIANT, RAGGED, EXTRAS>;
@@ -308,7 +309,7 @@ static hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* 
   }
   dim3 grid(BH * ((N + kBr - 1) / kBr));
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, (const bf16_t*)Q, (const bf16_t*)K,
-                     (const bf16_t*)V, (bf16_t*)O, LSE, N, alpha, beta, eps, ex);
+                     (const bf16_t*)V, (bf16_t*)O, LSE, N, alpha, beta, eps, ex, lay);
   return hipGetLastError();
 }
 
@@ -318,15 +319,15 @@ static hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* 
 hipError_t attn_fwd_dispatch(const void* Q, const void* K, const void* V, void* O, float* LSE,
                              int BH, int N, int d, int causal, float alpha, int variant,
                              float beta, float eps, float* O_hp, int* ones, int* fired,
-                             int single_rounding, hipStream_t st) {
+                             int single_rounding, Layout lay, hipStream_t st) {
   const bool extras = O_hp != nullptr || ones != nullptr || fired != nullptr || single_rounding != 0;
   const FwdExtras ex{O_hp, ones, fired, single_rounding};
   if (variant == 2) {   // whole-row detection: statistics pass, then the fixed-normaliser pass
 #define CASE2(DD, CC)                                                                           \
   if (d == DD && (causal != 0) == CC) {                                                          \
-    hipError_t e = launch_fwd<DD, CC, kRowStats, true, true>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, st); \
+    hipError_t e = launch_fwd<DD, CC, kRowStats, true, true>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, lay, st); \
     if (e != hipSuccess) return e;                                                               \
-    return launch_fwd<DD, CC, kFixedNorm, true, true>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, st); \
+    return launch_fwd<DD, CC, kFixedNorm, true, true>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, lay, st); \
   }
     CASE2(64, false) CASE2(64, true) CASE2(128, false) CASE2(128, true)
 #undef CASE2
@@ -334,9 +335,9 @@ hipError_t attn_fwd_dispatch(const void* Q, const void* K, const void* V, void* 
   }
 #define CASE(DD, CC, VV)                                                                      \
   if (d == DD && (causal != 0) == CC && variant == VV) {                                       \
-    if (extras) return launch_fwd<DD, CC, VV, true, true>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, st); \
-    return (N % kBr) ? launch_fwd<DD, CC, VV, true, false>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, st) \
-                     : launch_fwd<DD, CC, VV, false, false>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, st); \
+    if (extras) return launch_fwd<DD, CC, VV, true, true>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, lay, st); \
+    return (N % kBr) ? launch_fwd<DD, CC, VV, true, false>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, lay, st) \
+                     : launch_fwd<DD, CC, VV, false, false>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, lay, st); \
   }
   CASE(64, false, 0) CASE(64, false, 1) CASE(64, true, 0) CASE(64, true, 1)
   CASE(128, false, 0) CASE(128, false, 1) CASE(128, true, 0) CASE(128, true, 1)

@@ -264,3 +264,41 @@ def test_whole_row_detection_sees_ties_that_straddle_tiles(lib):
     O64, _ = exact.forward(xs["Q"], xs["K"], xs["V"], 0.125, False)
     for got in (tile, row):
         assert metrics.max_abs(_np(got["O"][0, 0]), O64) <= TOL_ABS
+
+
+@pytest.mark.parametrize("d,causal,N", [(64, True, 384), (128, True, 256), (128, False, 200), (64, False, 129)])
+def test_strided_layouts_give_bit_identical_results(lib, d, causal, N):
+    """attn_fwd_strided / attn_bwd_strided on (a) a [B,N,H,d] buffer and (b) views into one fused
+    [B,N,3,H,d] projection buffer, against the contiguous [B,H,N,d] entry points on the same
+    values: same arithmetic, so the results are equal bit for bit; memory around the strided
+    outputs is left untouched."""
+    B, H = 2, 3
+    g = torch.Generator().manual_seed(900 + N + d)
+    alpha = 1.0 / np.sqrt(d)
+    qkv = (1.1 * torch.randn((B, N, 3, H, d), generator=g)).to(torch.bfloat16).to(DEV)
+    dO_bnhd = torch.randn((B, N, H, d), generator=g).to(torch.bfloat16).to(DEV)
+    c = {k: qkv[:, :, i].permute(0, 2, 1, 3).contiguous() for i, k in enumerate(("Q", "K", "V"))}   # [B,H,N,d] copies
+    c["dO"] = dO_bnhd.permute(0, 2, 1, 3).contiguous()
+    for variant in (0, 1):
+        O_ref, L_ref = lib.attn_fwd(c["Q"], c["K"], c["V"], causal, alpha, variant)
+        dQ_ref, dK_ref, dV_ref = lib.attn_bwd(c["Q"], c["K"], c["V"], O_ref, c["dO"], L_ref, causal, alpha, variant)
+        # (a) plain [B,N,H,d] tensors seen as [B,H,N,d]
+        a = {k: v.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for k, v in c.items()}
+        assert a["Q"].stride() == (N * H * d, d, H * d, 1)
+        O_a, L_a = lib.attn_fwd_strided(a["Q"], a["K"], a["V"], causal, alpha, variant)
+        dQ_a, dK_a, dV_a = lib.attn_bwd_strided(a["Q"], a["K"], a["V"], O_a, a["dO"], L_a, causal, alpha, variant)
+        torch.cuda.synchronize()
+        assert O_a.stride() == a["Q"].stride()
+        for got, ref in ((O_a, O_ref), (dQ_a, dQ_ref), (dK_a, dK_ref), (dV_a, dV_ref)):
+            assert torch.equal(got, ref)
+        assert torch.equal(L_a, L_ref)
+    # (b) forward straight from the fused projection buffer, output into a canary-filled fused buffer
+    v = {k: qkv[:, :, i].permute(0, 2, 1, 3) for i, k in enumerate(("Q", "K", "V"))}
+    assert v["Q"].stride() == (N * 3 * H * d, d, 3 * H * d, 1)
+    out = torch.full((B, N, 3, H, d), 777.0, dtype=torch.bfloat16, device=DEV)
+    O_b = out[:, :, 1].permute(0, 2, 1, 3)
+    lib.attn_fwd_strided(v["Q"], v["K"], v["V"], causal, alpha, 1, O=O_b)
+    torch.cuda.synchronize()
+    O_ref, _ = lib.attn_fwd(c["Q"], c["K"], c["V"], causal, alpha, 1)
+    assert torch.equal(O_b, O_ref)
+    assert (out[:, :, 0] == 777.0).all() and (out[:, :, 2] == 777.0).all()

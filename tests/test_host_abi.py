@@ -67,6 +67,8 @@ def test_argument_validation_happens_on_the_host(binding):
     assert fwd(None, None, None, None, None, 0, 5, 128, 64) == OK      # empty batch: no-op
     ex = lambda beta, eps: lib.attn_fwd_ex(q, p, p, p, p, 1, 1, 128, 64, 1, 0.125, 1, beta, eps, None)
     assert ex(1.0, 1e-3) == BAD and ex(2.0, -1.0) == BAD and ex(float("nan"), 1e-3) == BAD
+    ptrs_for_strided = [ctypes.c_void_p(0x1000 * (i + 1)) for i in range(9)]
+    ws_for_strided = ctypes.c_void_p(0x100000)
     opt = lambda ohp, ones, fired, flags=0, O=q: lib.attn_fwd_opt(p, p, p, O, p, ohp, ones, fired, 1, 1, 128, 64, 1, 0.125, 0, 2.0, 1e-3, flags, None)
     assert opt(None, None, None, flags=2) == BAD                 # unknown flag bit
     assert opt(mis, None, None) == BAD                           # misaligned optional output
@@ -77,6 +79,10 @@ def test_argument_validation_happens_on_the_host(binding):
     assert lib.attn_delta_hp(None, p, q, 1, 1, 128, 64, None) == NULL
     assert lib.attn_delta_hp(p, p, p, 1, 1, 128, 64, None) == BAD  # delta aliases an input
     assert lib.attn_delta_hp(None, None, None, 0, 3, 128, 64, None) == OK
+    fs = lambda sb, sh, sn, d=64: lib.attn_fwd_strided(p, p, p, q, p, sb, sh, sn, 1, 1, 128, d, 1, 0.125, 0, 2.0, 1e-3, None)
+    assert fs(0, 64, 64) == BAD and fs(8192, 8192, 60) == BAD and fs(8192, 8192, 32) == BAD   # zero, not a multiple of 8, rows overlap
+    assert fs(8192, 8192, 1 << 24) == BAD and fs(8192, 8192, 96, d=96) == UNSUP
+    assert lib.attn_bwd_strided(*ptrs_for_strided, ws_for_strided, 4096, 8192, 8192, 4, 1, 1, 128, 64, 1, 0.125, 0, None) == BAD
     rc = lambda *a: lib.attn_delta_recompute(*a, 1, 1, 128, 64, 1, 0.125, None)
     assert rc(p, p, p, p, p, None) == NULL and rc(p, p, p, p, p, p) == BAD and rc(p, p, p, mis, p, q) == BAD
     assert lib.attn_delta_recompute(p, p, p, p, p, q, 1, 1, 128, 64, 1, -1.0, None) == BAD
