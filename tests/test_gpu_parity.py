@@ -43,6 +43,8 @@ def head_np(x, b, h):
 
 
 def check_head(got, x, b, h, causal, alpha, variant, beta=2.0, eps=1e-3, emu=True, label=""):
+    # the whole-row variant (2) is Alg. 3 with the key tile equal to the row
+    emu_variant, emu_Bc = (1, None) if variant == 2 else (variant, 64)
     xs = head_np(x, b, h)
     N = xs["Q"].shape[0]
     ref = exact.forward_backward(xs["Q"], xs["K"], xs["V"], xs["dO"], alpha, causal,
@@ -50,7 +52,7 @@ def check_head(got, x, b, h, causal, alpha, variant, beta=2.0, eps=1e-3, emu=Tru
     refs = {"O": ref[0], "dQ": ref[2], "dK": ref[3], "dV": ref[4]}
     emus = None
     if emu:
-        f = flash.forward(xs["Q"], xs["K"], xs["V"], alpha, causal, variant, beta, eps, Bc=64)
+        f = flash.forward(xs["Q"], xs["K"], xs["V"], alpha, causal, emu_variant, beta, eps, Bc=emu_Bc)
         g = flash.backward(xs["Q"], xs["K"], xs["V"], f["O"], xs["dO"], f["L"], alpha, causal, Bc=64)
         emus = {"O": f["O"], "dQ": g[0], "dK": g[1], "dV": g[2]}
     for name, r in refs.items():
@@ -284,3 +286,24 @@ def test_rejects_unsupported_shapes(lib):
     x = torch.zeros((0, 4, 128, 64), dtype=torch.bfloat16, device=DEV)
     O, L = lib.attn_fwd(x, x, x, True, 0.125, 0)
     assert O.numel() == 0
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_shapes_against_the_oracle(lib, seed):
+    """Shapes, scales and flags drawn from a seed: every head against the fp64 oracle."""
+    rng = np.random.default_rng(4242 + seed)
+    B, H = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+    N = int(rng.integers(1, 420))
+    d = int(rng.choice([64, 128]))
+    causal = bool(rng.integers(0, 2))
+    variant = int(rng.integers(0, 3))
+    scale = float(rng.choice([0.6, 1.0, 1.6]))
+    g = torch.Generator().manual_seed(int(rng.integers(0, 2 ** 31)))
+    x = {k: (scale * torch.randn((B, H, N, d), generator=g)).to(torch.bfloat16).to(DEV) for k in ("Q", "K", "V", "dO")}
+    alpha = 1.0 / np.sqrt(d)
+    got = run_gpu(lib, x, causal, alpha, variant)
+    label = f"random seed {seed}: B{B} H{H} N{N} d{d} causal={causal} variant={variant} scale={scale}"
+    print(label)
+    for b in range(B):
+        for h in range(H):
+            check_head(got, x, b, h, causal, alpha, variant, label=label)
