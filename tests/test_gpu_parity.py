@@ -307,3 +307,39 @@ def test_random_shapes_against_the_oracle(lib, seed):
     for b in range(B):
         for h in range(H):
             check_head(got, x, b, h, causal, alpha, variant, label=label)
+
+
+def test_step_is_capturable_in_a_graph(lib):
+    """The library neither allocates nor synchronises, so a forward + backward can be captured
+    into a HIP graph; several replays, with eager work between them, reproduce the eager result."""
+    w = synth.WORKLOADS["gpt2s"]
+    x = synth.make(w, DEV)
+    B, H, N, d = x["Q"].shape
+    O = torch.empty_like(x["Q"]); dQ = torch.empty_like(O); dK = torch.empty_like(O); dV = torch.empty_like(O)
+    L = torch.empty((B, H, N), dtype=torch.float32, device=DEV)
+    ws = torch.empty(max(256, lib.bwd_workspace_bytes(B, H, N, d)), dtype=torch.uint8, device=DEV)
+
+    def step():
+        lib.attn_fwd(x["Q"], x["K"], x["V"], w.causal, w.alpha, 1, O=O, LSE=L)
+        lib.attn_bwd(x["Q"], x["K"], x["V"], O, x["dO"], L, w.causal, w.alpha, 1, dQ=dQ, dK=dK, dV=dV, workspace=ws)
+
+    step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (O, L, dQ, dK, dV)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(3):
+        for t in (O, dQ, dK, dV):
+            t.fill_(7.0)                       # eager work between the replays
+        L.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((O, L, dQ, dK, dV), ref):
+            assert torch.equal(got, want)
