@@ -302,3 +302,40 @@ def test_strided_layouts_give_bit_identical_results(lib, d, causal, N):
     O_ref, _ = lib.attn_fwd(c["Q"], c["K"], c["V"], causal, alpha, 1)
     assert torch.equal(O_b, O_ref)
     assert (out[:, :, 0] == 777.0).all() and (out[:, :, 2] == 777.0).all()
+
+
+def test_autograd_wrapper(lib):
+    """`attention()` under torch.autograd: gradients of a scalar loss equal what attn_bwd returns
+    for the same dO, for contiguous inputs and for [B,N,H,d]-backed views; a few optimiser steps
+    on q run through."""
+    from paper_2510_04212_amd.autograd import attention
+    B, H, N, d = 2, 3, 256, 64
+    g = torch.Generator().manual_seed(31)
+    base = {k: torch.randn((B, N, H, d), generator=g).to(torch.bfloat16).to(DEV) for k in ("q", "k", "v", "w")}
+    for layout in ("bhnd", "bnhd"):
+        if layout == "bhnd":
+            t = {k: x.permute(0, 2, 1, 3).contiguous() for k, x in base.items()}
+        else:
+            t = {k: x.permute(0, 2, 1, 3) for k, x in base.items()}           # views, no copy
+        q, k, v = (t[n].detach().requires_grad_(True) for n in ("q", "k", "v"))
+        o = attention(q, k, v, causal=True, variant=lib.MITIGATED)
+        loss = (o.float() * t["w"].float()).sum()
+        loss.backward()
+        torch.cuda.synchronize()
+        # the same through the C ABI by hand, dO = w
+        qc, kc, vc, wc = (t[n].contiguous() for n in ("q", "k", "v", "w"))
+        O, L = lib.attn_fwd(qc, kc, vc, True, 1.0 / np.sqrt(d), lib.MITIGATED)
+        dQ, dK, dV = lib.attn_bwd(qc, kc, vc, O, wc, L, True, 1.0 / np.sqrt(d), lib.MITIGATED)
+        assert torch.equal(o, O)
+        assert torch.equal(q.grad, dQ) and torch.equal(k.grad, dK) and torch.equal(v.grad, dV)
+    q = base["q"].permute(0, 2, 1, 3).contiguous().float().requires_grad_(True)
+    opt = torch.optim.SGD([q], lr=1e-2)
+    first = None
+    for _ in range(3):
+        opt.zero_grad()
+        o = attention(q.to(torch.bfloat16), t["k"].contiguous(), t["v"].contiguous())
+        loss = (o.float() ** 2).mean()
+        loss.backward()
+        opt.step()
+        first = loss.item() if first is None else first
+    assert np.isfinite(loss.item()) and loss.item() <= first
