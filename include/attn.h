@@ -203,6 +203,23 @@ int attn_bwd_strided(const void* Q, const void* K, const void* V, const void* O,
                      int B, int H, int N, int d, int causal, float softmax_scale, int variant,
                      void* stream);
 
+/*
+ * Grouped-query attention (multi-query when H_kv == 1): Q, O, dO, dQ have H heads, K, V, dK, dV
+ * have H_kv heads, H a multiple of H_kv; query head h attends to key/value head h / (H / H_kv).
+ * Contiguous layouts [B,H,N,d] and [B,H_kv,N,d]; LSE and the workspace's delta are [B,H,N].
+ * Forward and dQ are the ordinary kernels reading the shared head; dK and dV are accumulated in
+ * float32 over the query heads of a group inside one work-group and rounded to bf16 once.
+ * H_kv == H is exactly attn_fwd_ex / attn_bwd.  ATTN_ERR_BAD_ARG if H is not a multiple of H_kv.
+ */
+int attn_fwd_gqa(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                 int B, int H, int H_kv, int N, int d, int causal, float softmax_scale, int variant,
+                 float beta, float eps, void* stream);
+int attn_bwd_gqa(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                 const float* LSE, void* dQ, void* dK, void* dV,
+                 void* workspace, size_t workspace_bytes,
+                 int B, int H, int H_kv, int N, int d, int causal, float softmax_scale, int variant,
+                 void* stream);
+
 /* Human-readable name of an attn_status (static storage, never NULL). */
 const char* attn_status_string(int status);
 

@@ -43,6 +43,10 @@ _lib.attn_fwd_strided.argtypes = [_vp] * 5 + [_ll, _ll, _ll, _i, _i, _i, _i, _i,
 _lib.attn_fwd_strided.restype = _i
 _lib.attn_bwd_strided.argtypes = [_vp] * 9 + [_vp, _sz, _ll, _ll, _ll, _i, _i, _i, _i, _i, _f, _i, _vp]
 _lib.attn_bwd_strided.restype = _i
+_lib.attn_fwd_gqa.argtypes = [_vp] * 5 + [_i, _i, _i, _i, _i, _i, _f, _i, _f, _f, _vp]
+_lib.attn_fwd_gqa.restype = _i
+_lib.attn_bwd_gqa.argtypes = [_vp] * 9 + [_vp, _sz, _i, _i, _i, _i, _i, _i, _f, _i, _vp]
+_lib.attn_bwd_gqa.restype = _i
 _lib.attn_bwd.argtypes = [_vp] * 9 + [_vp, _sz, _i, _i, _i, _i, _i, _f, _i, _vp]
 _lib.attn_bwd.restype = _i
 _lib.attn_bwd_dkdv.argtypes = [_vp] * 8 + [_i, _i, _i, _i, _i, _f, _vp]
@@ -61,6 +65,7 @@ FWD_SINGLE_ROUNDING = 1
 EXPORTS = ["attn_fwd", "attn_fwd_ex", "attn_fwd_opt", "attn_delta", "attn_delta_hp",
            "attn_delta_recompute", "attn_bwd",
            "attn_bwd_dkdv", "attn_bwd_dq", "attn_fwd_strided", "attn_bwd_strided",
+           "attn_fwd_gqa", "attn_bwd_gqa",
            "attn_bwd_workspace_bytes",
            "attn_status_string", "attn_fwd_key_tile"]
 
@@ -283,4 +288,38 @@ def attn_bwd_strided(Q, K, V, O, dO, LSE, causal, softmax_scale, variant=STANDAR
                                  _ptr(dK), _ptr(dV), _ptr(workspace), workspace.numel(), sb, sh, sn,
                                  B, H, N, d, int(bool(causal)), float(softmax_scale), int(variant),
                                  _stream(stream)))
+    return dQ, dK, dV
+
+
+def attn_fwd_gqa(Q, K, V, causal, softmax_scale, variant=STANDARD, beta=None, eps=None, stream=None):
+    """Grouped-query forward: Q [B,H,N,d], K and V [B,H_kv,N,d] (contiguous)."""
+    B, H, N, d = _bhnd(Q, "Q")
+    Bk, Hkv, Nk, dk = _bhnd(K, "K")
+    if _bhnd(V, "V") != K.shape or (Bk, Nk, dk) != (B, N, d):
+        raise ValueError("K and V must be [B,H_kv,N,d] with the batch, length and head size of Q")
+    O = torch.empty_like(Q)
+    LSE = torch.empty((B, H, N), dtype=torch.float32, device=Q.device)
+    _check(_lib.attn_fwd_gqa(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), B, H, Hkv, N, d,
+                             int(bool(causal)), float(softmax_scale), int(variant),
+                             float(DEFAULT_BETA if beta is None else beta),
+                             float(DEFAULT_EPS if eps is None else eps), _stream(stream)))
+    return O, LSE
+
+
+def attn_bwd_gqa(Q, K, V, O, dO, LSE, causal, softmax_scale, variant=STANDARD, workspace=None, stream=None):
+    """Grouped-query backward: dQ like Q, dK and dV like K."""
+    B, H, N, d = _bhnd(Q, "Q")
+    Hkv = _bhnd(K, "K")[1]
+    for n, t in (("O", O), ("dO", dO)):
+        if _bhnd(t, n) != (B, H, N, d):
+            raise ValueError(f"{n} shape differs from Q")
+    if _bhnd(V, "V") != K.shape:
+        raise ValueError("V shape differs from K")
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(K)
+    need = bwd_workspace_bytes(B, H, N, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Q.device)
+    _check(_lib.attn_bwd_gqa(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK),
+                             _ptr(dV), _ptr(workspace), workspace.numel(), B, H, Hkv, N, d,
+                             int(bool(causal)), float(softmax_scale), int(variant), _stream(stream)))
     return dQ, dK, dV

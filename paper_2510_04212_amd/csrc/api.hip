@@ -10,6 +10,8 @@ struct Layout {
   long long sb, sh;
   int sn;
   int H;
+  long long sb_kv, sh_kv;   // batch / head strides of K, V, dK, dV
+  int group;                // query heads per key/value head
 };
 
 hipError_t attn_fwd_dispatch(const void*, const void*, const void*, void*, float*, int, int, int,
@@ -31,8 +33,10 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-Layout contiguous(int H, int N, int d) {
-  return Layout{(long long)H * N * d, (long long)N * d, d, H};
+Layout contiguous(int H, int N, int d, int H_kv = 0) {
+  if (H_kv <= 0) H_kv = H;
+  return Layout{(long long)H * N * d, (long long)N * d, d, H,
+                (long long)H_kv * N * d, (long long)N * d, H / H_kv};
 }
 
 // Strides of the strided entry points: positive multiples of 8 elements (rows start on 16-byte
@@ -116,7 +120,7 @@ extern "C" int attn_fwd_strided(const void* Q, const void* K, const void* V, voi
                                 int variant, float beta, float eps, void* stream) {
   if (B < 0 || H < 0 || N < 0 || d < 0) return ATTN_ERR_BAD_ARG;
   if (!strides_ok(stride_b, stride_h, stride_n, d)) return ATTN_ERR_BAD_ARG;
-  const Layout lay{stride_b, stride_h, (int)stride_n, H};
+  const Layout lay{stride_b, stride_h, (int)stride_n, H, stride_b, stride_h, 1};
   return fwd_entry(Q, K, V, O, LSE, nullptr, nullptr, nullptr, B, H, N, d, causal, softmax_scale,
                    variant, beta, eps, 0u, &lay, stream);
 }
@@ -264,7 +268,7 @@ extern "C" int attn_bwd_strided(const void* Q, const void* K, const void* V, con
                                 int variant, void* stream) {
   if (B < 0 || H < 0 || N < 0 || d < 0) return ATTN_ERR_BAD_ARG;
   if (!strides_ok(stride_b, stride_h, stride_n, d)) return ATTN_ERR_BAD_ARG;
-  const Layout lay{stride_b, stride_h, (int)stride_n, H};
+  const Layout lay{stride_b, stride_h, (int)stride_n, H, stride_b, stride_h, 1};
   return bwd_entry(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, H, N, d, causal,
                    softmax_scale, variant, &lay, stream);
 }
@@ -286,4 +290,28 @@ extern "C" int attn_delta_recompute(const void* Q, const void* K, const void* V,
                                                softmax_scale, contiguous(H, N, d),
                                                static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+// Grouped-query attention: H query heads, H_kv key/value heads.
+static bool gqa_heads_ok(int H, int H_kv) { return H_kv >= 1 && H >= H_kv && H % H_kv == 0; }
+
+extern "C" int attn_fwd_gqa(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                            int B, int H, int H_kv, int N, int d, int causal, float softmax_scale,
+                            int variant, float beta, float eps, void* stream) {
+  if (B < 0 || H < 0 || H_kv < 0 || N < 0 || d < 0) return ATTN_ERR_BAD_ARG;
+  if (B > 0 && H > 0 && !gqa_heads_ok(H, H_kv)) return ATTN_ERR_BAD_ARG;
+  const Layout lay = (B > 0 && H > 0) ? contiguous(H, N, d, H_kv) : contiguous(1, N, d);
+  return fwd_entry(Q, K, V, O, LSE, nullptr, nullptr, nullptr, B, H, N, d, causal, softmax_scale,
+                   variant, beta, eps, 0u, &lay, stream);
+}
+
+extern "C" int attn_bwd_gqa(const void* Q, const void* K, const void* V, const void* O,
+                            const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
+                            void* workspace, size_t workspace_bytes, int B, int H, int H_kv, int N,
+                            int d, int causal, float softmax_scale, int variant, void* stream) {
+  if (B < 0 || H < 0 || H_kv < 0 || N < 0 || d < 0) return ATTN_ERR_BAD_ARG;
+  if (B > 0 && H > 0 && !gqa_heads_ok(H, H_kv)) return ATTN_ERR_BAD_ARG;
+  const Layout lay = (B > 0 && H > 0) ? contiguous(H, N, d, H_kv) : contiguous(1, N, d);
+  return bwd_entry(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, H, N, d, causal,
+                   softmax_scale, variant, &lay, stream);
 }

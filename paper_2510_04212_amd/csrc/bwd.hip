@@ -43,7 +43,9 @@ DEVI void store_acc_T(bf16_t* dst_row, const f32x16 (&acc)[D / 32], float scale,
     }
 }
 
-template <int D, bool CAUSAL, bool RAGGED>
+// GROUPED: grouped-query attention (lay.group > 1): the work-group serves several query heads.
+// Kept out of the ordinary kernel so that its tile loop has a fixed head and no bookkeeping.
+template <int D, bool CAUSAL, bool RAGGED, bool GROUPED>
 __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
@@ -63,17 +65,18 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
 
   const int nkt = (N + kKeysPerWG - 1) / kKeysPerWG;   // N need not be a multiple of the block
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
-  const int bh = wg / nkt;
+  // one work-group per (batch, key/value head, key block); with grouped queries it serves the
+  // `group` query heads that share this key/value head, one after the other
+  const int bhk = wg / nkt;
+  const int group = GROUPED ? lay.group : 1;
+  const int Hkv = lay.H / group;
+  const int bq0 = (bhk / Hkv) * lay.H + (bhk % Hkv) * group;   // first of those query heads
   // early key blocks see the most queries: heavy first
-  const int kt = (wg % nkt + (CAUSAL ? small_grid_rotation(bh, nkt, gridDim.x, D == 128 ? 384 : 768) : 0)) % nkt;
+  const int kt = (wg % nkt + (CAUSAL ? small_grid_rotation(bhk, nkt, gridDim.x, D == 128 ? 384 : 768) : 0)) % nkt;
   const int k0 = kt * kKeysPerWG;
   const int kw = k0 + 32 * wave;
-  const size_t head_off = head_base(lay, bh);
+  const size_t head_off = head_base_kv(lay, bq0);              // K, V, dK, dV
   const int sn = lay.sn;
-  const bf16_t* Qh = Q + head_off;
-  const bf16_t* dOh = dO + head_off;
-  const float* Lh = LSE + (size_t)bh * N;
-  const float* Dh = delta + (size_t)bh * N;
 
   // K_j^T / V_j^T fragments (B operands): lane (r,h) holds K[kw + r][16kc + 8h .. +7]
   // (keys past the sequence end read the last row; their gradients are not stored)
@@ -102,33 +105,48 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
   loader.init(tid, sn);
   FragOffsets<D> fo;
   init_frag_offsets<D>(fo, lane);
-  auto load_tile = [&](int t, int buf) {
-    loader.template load_rows<RAGGED>(ldsQ + buf * TILE_BYTES, Qh, t * kQTile, N, tid);
-    loader.template load_rows<RAGGED>(ldsdO + buf * TILE_BYTES, dOh, t * kQTile, N, tid);
+  // Current query head: its first element in Q / dO and in LSE / delta.  With GROUPED the
+  // work-group moves on to the next head of its group (at distance lay.sh and N) after tile
+  // nt - 1, without breaking the double buffering: `step` counts tiles over all heads.
+  const bf16_t* Qh = Q + head_base(lay, bq0);
+  const bf16_t* dOh = dO + head_base(lay, bq0);
+  const float* Lh = LSE + (size_t)bq0 * N;
+  const float* Dh = delta + (size_t)bq0 * N;
+  const int total = group * (nt - t0);
+  auto load_tile = [&](const bf16_t* Qp, const bf16_t* dOp, const float* Lp, const float* Dp, int t, int buf) {
+    loader.template load_rows<RAGGED>(ldsQ + buf * TILE_BYTES, Qp, t * kQTile, N, tid);
+    loader.template load_rows<RAGGED>(ldsdO + buf * TILE_BYTES, dOp, t * kQTile, N, tid);
     const int row = t * kQTile + (tid & (kQTile - 1));
     const int rowc = (RAGGED && row >= N) ? N - 1 : row;
-    if (tid < kQTile) sreg = Lh[rowc] * kLog2e;
-    else if (tid < 2 * kQTile) sreg = -Dh[rowc];   // LDS holds -delta
+    if (tid < kQTile) sreg = Lp[rowc] * kLog2e;
+    else if (tid < 2 * kQTile) sreg = -Dp[rowc];   // LDS holds -delta
   };
   auto store_stats = [&](int buf) {
     if (tid < kQTile) ldsL[buf * kQTile + tid] = sreg;
     else if (tid < 2 * kQTile) ldsD[buf * kQTile + tid - kQTile] = sreg;
   };
-  load_tile(t0, 0);
+  load_tile(Qh, dOh, Lh, Dh, t0, 0);
   store_stats(0);
   wait_vmem();
   __syncthreads();
 
   // One query tile; BUF (which LDS buffer holds it) is a compile-time constant so that every LDS
   // address is a precomputed per-lane offset plus an immediate.
-  auto tile_step = [&](auto buf_c, int t) {
+  auto tile_step = [&](auto buf_c, int t, int step) {
     constexpr int buf = decltype(buf_c)::value;
+    const bool has_next = (step + 1 < total);
+    if (has_next) {
+      if (GROUPED && t + 1 == nt) {   // on to the next query head of the group
+        Qh += lay.sh; dOh += lay.sh; Lh += N; Dh += N;
+        load_tile(Qh, dOh, Lh, Dh, t0, buf ^ 1);
+      } else {
+        load_tile(Qh, dOh, Lh, Dh, t + 1, buf ^ 1);
+      }
+    }
     const char* tQ = smem + buf * TILE_BYTES;
     const char* tdO = smem + (2 + buf) * TILE_BYTES;
     const float* tL = reinterpret_cast<const float*>(smem + 4 * TILE_BYTES) + buf * kQTile;
     const float* tD = reinterpret_cast<const float*>(smem + 4 * TILE_BYTES) + 2 * kQTile + buf * kQTile;
-    const bool has_next = (t + 1 < nt);
-    if (has_next) load_tile(t + 1, buf ^ 1);
     const int qt0 = t * kQTile;
     // one 32-query block against this wave's 32 keys; DIAG: the block crosses the diagonal
     auto qblock = [&](auto diag_c, int qb) {
@@ -293,9 +311,21 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
     wait_vmem();
     __syncthreads();
   };
-  for (int t = t0; t < nt; t += 2) {
-    tile_step(std::integral_constant<int, 0>{}, t);
-    if (t + 1 < nt) tile_step(std::integral_constant<int, 1>{}, t + 1);
+  if (!GROUPED) {
+    for (int t = t0; t < nt; t += 2) {
+      tile_step(std::integral_constant<int, 0>{}, t, t - t0);
+      if (t + 1 < nt) tile_step(std::integral_constant<int, 1>{}, t + 1, t + 1 - t0);
+    }
+  } else {
+    int t = t0;
+    for (int step = 0; step < total; step += 2) {
+      tile_step(std::integral_constant<int, 0>{}, t, step);
+      t = (t + 1 == nt) ? t0 : t + 1;
+      if (step + 1 < total) {
+        tile_step(std::integral_constant<int, 1>{}, t, step + 1);
+        t = (t + 1 == nt) ? t0 : t + 1;
+      }
+    }
   }
   if (!RAGGED || kw + r < N) {
     store_acc_T<D>(dV + head_off + (size_t)(kw + r) * sn, dVt, 1.0f, h);
@@ -329,8 +359,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
   const int qw = q0 + 32 * wave;
   const size_t head_off = head_base(lay, bh);
   const int sn = lay.sn;
-  const bf16_t* Kh = K + head_off;
-  const bf16_t* Vh = V + head_off;
+  const bf16_t* Kh = K + head_base_kv(lay, bh);
+  const bf16_t* Vh = V + head_base_kv(lay, bh);
 
   // Q_i^T / dO_i^T fragments (B operands): lane (r,h) holds Q[qw + r][16kc + 8h .. +7]
   // (rows past the sequence end read the last row; their dQ is not stored)
@@ -450,16 +480,16 @@ static hipError_t set_smem(KernT kern, int smem, bool& done) {
   return e;
 }
 
-template <int D, bool CAUSAL, bool RAGGED>
+template <int D, bool CAUSAL, bool RAGGED, bool GROUPED>
 static hipError_t launch_dkdv(const void* Q, const void* K, const void* V, const void* dO,
                               const float* LSE, const float* delta, void* dK, void* dV, int BH,
                               int N, float alpha, Layout lay, hipStream_t st) {
   constexpr int smem = 4 * kQTile * D * 2 + 4 * kQTile * (int)sizeof(float);
   static bool set = false;
-  auto k = attn_bwd_dkdv_kernel<D, CAUSAL, RAGGED>;
+  auto k = attn_bwd_dkdv_kernel<D, CAUSAL, RAGGED, GROUPED>;
   hipError_t e;
   if ((e = set_smem(k, smem, set)) != hipSuccess) return e;
-  hipLaunchKernelGGL(k, dim3(BH * ((N + kKeysPerWG - 1) / kKeysPerWG)), dim3(256), smem, st, (const bf16_t*)Q,
+  hipLaunchKernelGGL(k, dim3((BH / lay.group) * ((N + kKeysPerWG - 1) / kKeysPerWG)), dim3(256), smem, st, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
                      (bf16_t*)dK, (bf16_t*)dV, N, alpha, lay);
   return hipGetLastError();
@@ -487,9 +517,17 @@ hipError_t attn_bwd_dkdv_dispatch(const void* Q, const void* K, const void* V, c
                                   int BH, int N, int d, int causal, float alpha, Layout lay,
                                   hipStream_t st) {
   const bool ragged = (N % kKeysPerWG) != 0;     // the aligned kernels carry no bounds handling
+  if (lay.group > 1) {   // grouped queries: the bounds-checking instantiation serves every N
+#define CASEG(DD, CC)                                 \
+  if (d == DD && (causal != 0) == CC)                 \
+    return launch_dkdv<DD, CC, true, true>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, lay, st);
+    CASEG(64, false) CASEG(64, true) CASEG(128, false) CASEG(128, true)
+#undef CASEG
+    return hipErrorInvalidValue;
+  }
 #define CASE(DD, CC, RR)                                                \
   if (d == DD && (causal != 0) == CC && ragged == RR)                   \
-    return launch_dkdv<DD, CC, RR>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, lay, st);
+    return launch_dkdv<DD, CC, RR, false>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, lay, st);
   CASE(64, false, false) CASE(64, false, true) CASE(64, true, false) CASE(64, true, true)
   CASE(128, false, false) CASE(128, false, true) CASE(128, true, false) CASE(128, true, true)
 #undef CASE

@@ -134,13 +134,22 @@ DEVI float bf16_bits_to_float(unsigned short b) { return __uint_as_float(((unsig
 // b*sb + h*sh + n*sn + k (the last dimension is contiguous).  [B,H,N,d] contiguous is
 // (H*N*d, N*d, d); [B,N,H,d] is (N*H*d, d, H*d).  float32 per-row tensors (LSE, delta) and the
 // optional float32 / int32 outputs are always contiguous [B,H,N(,d)].
+// Grouped-query attention: K, V, dK, dV have H / group heads with their own batch / head strides
+// (sb_kv, sh_kv); query head h uses key/value head h / group.  group = 1 is ordinary attention.
 struct Layout {
   long long sb, sh;
   int sn;
   int H;
+  long long sb_kv, sh_kv;
+  int group;
 };
+// first element of query-side head bh = b*H + h
 DEVI size_t head_base(const Layout& lay, int bh) {
   return (size_t)(bh / lay.H) * (size_t)lay.sb + (size_t)(bh % lay.H) * (size_t)lay.sh;
+}
+// first element of the key/value head that query-side head bh attends to
+DEVI size_t head_base_kv(const Layout& lay, int bh) {
+  return (size_t)(bh / lay.H) * (size_t)lay.sb_kv + (size_t)((bh % lay.H) / lay.group) * (size_t)lay.sh_kv;
 }
 
 // Asynchronous copy of a 64-row x D bf16 tile from global memory straight into swizzled LDS
@@ -156,6 +165,15 @@ DEVI size_t head_base(const Layout& lay, int bh) {
 // both the fragment read-ahead and the overlap of the transfer with computation.  Hidden from
 // its bookkeeping, the transfer only makes the compiler's own vmcnt waits more conservative
 // (loads complete in order), and its completion is enforced explicitly by wait_vmem().
+// A pointer the caller knows to be the same in every lane, as a scalar-register value (the tile
+// loader's instruction takes its base address from scalar registers).
+DEVI const bf16_t* wave_uniform(const bf16_t* p) {
+  const unsigned long long u = reinterpret_cast<unsigned long long>(p);
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)u);
+  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(u >> 32));
+  return reinterpret_cast<const bf16_t*>(((unsigned long long)hi << 32) | lo);
+}
+
 template <int D> struct TileLoader {
   static constexpr int CH = D / 8;               // 16-byte chunks per row
   static constexpr int RPI = 64 / CH;            // rows per wave-instruction
@@ -197,7 +215,7 @@ template <int D> struct TileLoader {
   // reach past row N-1 and is then loaded clamped; otherwise every tile is known to be full.
   template <bool RAGGED>
   DEVI void load_rows(const char* tile, const bf16_t* tensor, int row0, int N, int tid) const {
-    const bf16_t* src = tensor + (size_t)row0 * sn;
+    const bf16_t* src = wave_uniform(tensor + (size_t)row0 * sn);
     if (!RAGGED || row0 + 64 <= N) load(tile, src);
     else load_clamped(tile, src, N - row0, tid);
   }

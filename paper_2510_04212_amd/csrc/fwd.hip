@@ -65,8 +65,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
   const size_t head_off = head_base(lay, bh);
   const int sn = lay.sn;
   const bf16_t* Qh = Q + head_off;
-  const bf16_t* Kh = K + head_off;
-  const bf16_t* Vh = V + head_off;
+  const bf16_t* Kh = K + head_base_kv(lay, bh);
+  const bf16_t* Vh = V + head_base_kv(lay, bh);
 
   TileLoader<D> loader;
   loader.init(tid, sn);

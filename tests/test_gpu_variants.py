@@ -339,3 +339,42 @@ def test_autograd_wrapper(lib):
         opt.step()
         first = loss.item() if first is None else first
     assert np.isfinite(loss.item()) and loss.item() <= first
+
+
+@pytest.mark.parametrize("H,Hkv,N,d,causal", [(4, 4, 256, 64, True), (6, 2, 320, 64, True), (4, 1, 200, 128, True),
+                                              (8, 2, 256, 128, False), (3, 1, 65, 64, False)])
+def test_grouped_query_attention(lib, H, Hkv, N, d, causal):
+    """attn_fwd_gqa / attn_bwd_gqa: O and dQ equal, bit for bit, ordinary attention on K, V repeated
+    for every query head of a group; dK, dV (summed over the group in float32, rounded once)
+    against the fp64 oracle's per-head gradients summed over the group."""
+    B = 2
+    group = H // Hkv
+    g = torch.Generator().manual_seed(555 + H * 10 + Hkv + N)
+    alpha = 1.0 / np.sqrt(d)
+    Q = torch.randn((B, H, N, d), generator=g).to(torch.bfloat16).to(DEV)
+    dO = torch.randn((B, H, N, d), generator=g).to(torch.bfloat16).to(DEV)
+    K = torch.randn((B, Hkv, N, d), generator=g).to(torch.bfloat16).to(DEV)
+    V = torch.randn((B, Hkv, N, d), generator=g).to(torch.bfloat16).to(DEV)
+    Kx, Vx = K.repeat_interleave(group, dim=1).contiguous(), V.repeat_interleave(group, dim=1).contiguous()
+    for variant in (0, 1):
+        O, L = lib.attn_fwd_gqa(Q, K, V, causal, alpha, variant)
+        dQ, dK, dV = lib.attn_bwd_gqa(Q, K, V, O, dO, L, causal, alpha, variant)
+        O_ref, L_ref = lib.attn_fwd(Q, Kx, Vx, causal, alpha, variant)
+        dQ_ref, dKx, dVx = lib.attn_bwd(Q, Kx, Vx, O_ref, dO, L_ref, causal, alpha, variant)
+        torch.cuda.synchronize()
+        assert dK.shape == K.shape and dV.shape == V.shape
+        assert torch.equal(O, O_ref) and torch.equal(L, L_ref) and torch.equal(dQ, dQ_ref)
+        if group == 1:
+            assert torch.equal(dK, dKx) and torch.equal(dV, dVx)
+        for (b, hk) in ((0, 0), (B - 1, Hkv - 1)):
+            dK64 = np.zeros((N, d)); dV64 = np.zeros((N, d))
+            for j in range(group):
+                h = hk * group + j
+                r = exact.forward_backward(_np(Q[b, h]), _np(K[b, hk]), _np(V[b, hk]), _np(dO[b, h]), alpha, causal)
+                dK64 += r[3]; dV64 += r[4]
+            for got, ref in ((dK[b, hk], dK64), (dV[b, hk], dV64)):
+                got = _np(got)
+                assert np.isfinite(got).all()
+                assert metrics.rel_l2(got, ref) <= TOL_REL
+                # a sum of `group` heads: magnitudes and bf16 steps grow with the group
+                assert metrics.max_abs(got, ref) <= max(TOL_ABS, 2.0 ** -8 * np.abs(ref).max())

@@ -83,6 +83,9 @@ def test_argument_validation_happens_on_the_host(binding):
     assert fs(0, 64, 64) == BAD and fs(8192, 8192, 60) == BAD and fs(8192, 8192, 32) == BAD   # zero, not a multiple of 8, rows overlap
     assert fs(8192, 8192, 1 << 24) == BAD and fs(8192, 8192, 96, d=96) == UNSUP
     assert lib.attn_bwd_strided(*ptrs_for_strided, ws_for_strided, 4096, 8192, 8192, 4, 1, 1, 128, 64, 1, 0.125, 0, None) == BAD
+    gq = lambda H, Hkv: lib.attn_fwd_gqa(p, p, p, q, p, 1, H, Hkv, 128, 64, 1, 0.125, 0, 2.0, 1e-3, None)
+    assert gq(6, 4) == BAD and gq(4, 0) == BAD and gq(2, 4) == BAD and gq(0, 0) == OK
+    assert lib.attn_bwd_gqa(*ptrs_for_strided, ws_for_strided, 4096, 1, 6, 4, 128, 64, 1, 0.125, 0, None) == BAD
     rc = lambda *a: lib.attn_delta_recompute(*a, 1, 1, 128, 64, 1, 0.125, None)
     assert rc(p, p, p, p, p, None) == NULL and rc(p, p, p, p, p, p) == BAD and rc(p, p, p, mis, p, q) == BAD
     assert lib.attn_delta_recompute(p, p, p, p, p, q, 1, 1, 128, 64, 1, -1.0, None) == BAD
