@@ -5,7 +5,7 @@ pass attn_bwd / attn_bwd_strided of the library (Alg. 1 or Alg. 3 forward, Alg. 
 arXiv 2510.04212); nothing is computed here.  q, k, v are bfloat16 CUDA tensors of logical
 shape [B, H, N, d]; they may be contiguous or share any batch / head / row strides with a
 contiguous last dimension (for instance `x.view(B, N, H, d).permute(0, 2, 1, 3)`), in which case
-no copy is made.
+no copy is made.  k and v may have fewer heads than q (grouped-query attention).
 """
 import math
 
@@ -22,6 +22,12 @@ def _same_layout(*ts):
 class _FlashAttention(torch.autograd.Function):
     @staticmethod
     def forward(ctx, q, k, v, causal, softmax_scale, variant, beta, eps):
+        if k.shape[1] != q.shape[1]:        # grouped-query attention: fewer key/value heads
+            q, k, v = q.contiguous(), k.contiguous(), v.contiguous()
+            o, lse = binding.attn_fwd_gqa(q, k, v, causal, softmax_scale, variant, beta, eps)
+            ctx.save_for_backward(q, k, v, o, lse)
+            ctx.args = (causal, softmax_scale, variant, "gqa")
+            return o
         strided = not (q.is_contiguous() and k.is_contiguous() and v.is_contiguous())
         if strided and not (_same_layout(q, k, v) and q.stride(3) == 1):
             q, k, v = q.contiguous(), k.contiguous(), v.contiguous()
@@ -38,7 +44,9 @@ class _FlashAttention(torch.autograd.Function):
     def backward(ctx, do):
         q, k, v, o, lse = ctx.saved_tensors
         causal, softmax_scale, variant, strided = ctx.args
-        if strided:
+        if strided == "gqa":
+            dq, dk, dv = binding.attn_bwd_gqa(q, k, v, o, do.contiguous(), lse, causal, softmax_scale, variant)
+        elif strided:
             if do.stride() != q.stride():
                 d2 = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
                 d2.copy_(do)

@@ -328,6 +328,17 @@ def test_autograd_wrapper(lib):
         dQ, dK, dV = lib.attn_bwd(qc, kc, vc, O, wc, L, True, 1.0 / np.sqrt(d), lib.MITIGATED)
         assert torch.equal(o, O)
         assert torch.equal(q.grad, dQ) and torch.equal(k.grad, dK) and torch.equal(v.grad, dV)
+    # grouped-query: 3 query heads on 1 key/value head
+    q = base["q"].permute(0, 2, 1, 3).contiguous().requires_grad_(True)
+    k1 = base["k"].permute(0, 2, 1, 3)[:, :1].contiguous().requires_grad_(True)
+    v1 = base["v"].permute(0, 2, 1, 3)[:, :1].contiguous().requires_grad_(True)
+    w = base["w"].permute(0, 2, 1, 3).contiguous()
+    o = attention(q, k1, v1, causal=True, variant=lib.STANDARD)
+    (o.float() * w.float()).sum().backward()
+    O, L = lib.attn_fwd_gqa(q.detach(), k1.detach(), v1.detach(), True, 1.0 / np.sqrt(d), lib.STANDARD)
+    dQ, dK, dV = lib.attn_bwd_gqa(q.detach(), k1.detach(), v1.detach(), O, w, L, True, 1.0 / np.sqrt(d), lib.STANDARD)
+    torch.cuda.synchronize()
+    assert torch.equal(o, O) and torch.equal(q.grad, dQ) and torch.equal(k1.grad, dK) and torch.equal(v1.grad, dV)
     q = base["q"].permute(0, 2, 1, 3).contiguous().float().requires_grad_(True)
     opt = torch.optim.SGD([q], lr=1e-2)
     first = None
