@@ -21,12 +21,10 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
 #define DEVI __device__ __forceinline__
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
 
 DEVI f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -127,8 +125,6 @@ DEVI float sum_with_partner32(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
-
-DEVI float bf16_bits_to_float(unsigned short b) { return __uint_as_float(((unsigned)b) << 16); }
 
 // Addressing of the bf16 tensors Q, K, V, O, dO, dQ, dK, dV: element (b, h, n, k) lives at
 // b*sb + h*sh + n*sn + k (the last dimension is contiguous).  [B,H,N,d] contiguous is
