@@ -17,6 +17,12 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Wno-unused-command-line-argument",
          # the tile loader's inline assembly names m0 as clobbered on purpose (it sets it)
          "-Wno-inline-asm"]
+# Per-source additions.  The backward kernels are long straight-line regions of matrix
+# instructions with their LDS reads placed by hand; the scheduler's "maximise instruction-level
+# parallelism" strategy keeps that order with fewer stalls than the default (occupancy-driven)
+# one: measured 2-3 % on the dK/dV kernel at d = 128, nothing lost elsewhere.  The forward is
+# faster with the default strategy.
+EXTRA_FLAGS = {"bwd.hip": ["-mllvm", "-amdgpu-sched-strategy=max-ilp"]}
 
 
 def build(verbose=True):
@@ -27,7 +33,7 @@ def build(verbose=True):
     procs = []
     for src in SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        cmd = [hipcc] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc] + FLAGS + EXTRA_FLAGS.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

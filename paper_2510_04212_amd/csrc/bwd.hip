@@ -64,272 +64,280 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
   const int r = lane & 31, h = lane >> 5;
 
   const int nkt = (N + kKeysPerWG - 1) / kKeysPerWG;   // N need not be a multiple of the block
+  // Under the causal mask key block kt meets nkt - kt query blocks' worth of tiles: a work-group
+  // takes block kt and then its mirror image nkt - 1 - kt, so that all work-groups carry the same
+  // load (and there are half as many to start and drain).
+  const int npw = CAUSAL ? (nkt + 1) / 2 : nkt;        // work-groups per key/value head
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
-  // one work-group per (batch, key/value head, key block); with grouped queries it serves the
-  // `group` query heads that share this key/value head, one after the other
-  const int bhk = wg / nkt;
+  // with grouped queries a work-group serves the `group` query heads that share its key/value
+  // head, one after the other
+  const int bhk = wg / npw;
   const int group = GROUPED ? lay.group : 1;
   const int Hkv = lay.H / group;
   const int bq0 = (bhk / Hkv) * lay.H + (bhk % Hkv) * group;   // first of those query heads
-  // early key blocks see the most queries: heavy first
-  const int kt = (wg % nkt + (CAUSAL ? small_grid_rotation(bhk, nkt, gridDim.x, D == 128 ? 384 : 768) : 0)) % nkt;
-  const int k0 = kt * kKeysPerWG;
-  const int kw = k0 + 32 * wave;
-  const size_t head_off = head_base_kv(lay, bq0);              // K, V, dK, dV
+  const int kt_first = wg % npw;
   const int sn = lay.sn;
-
-  // K_j^T / V_j^T fragments (B operands): lane (r,h) holds K[kw + r][16kc + 8h .. +7]
-  // (keys past the sequence end read the last row; their gradients are not stored)
-  const int keyc = (RAGGED && kw + r >= N) ? N - 1 : kw + r;
-  bf16x8 kf[D / 16], vf[D / 16];
-#pragma unroll
-  for (int kc = 0; kc < D / 16; ++kc) {
-    kf[kc] = *reinterpret_cast<const bf16x8*>(K + head_off + (size_t)keyc * sn + 16 * kc + 8 * h);
-    vf[kc] = *reinterpret_cast<const bf16x8*>(V + head_off + (size_t)keyc * sn + 16 * kc + 8 * h);
-  }
-  f32x16 dVt[D / 32], dKt[D / 32];
-#pragma unroll
-  for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { dVt[db][i] = 0.f; dKt[db][i] = 0.f; }
-
-  const int t0 = CAUSAL ? k0 / kQTile : 0;         // first query tile that sees any key of this block
-  const int nt = RAGGED ? (N + kQTile - 1) / kQTile : N / kQTile;
+  const size_t head_off = head_base_kv(lay, bq0);              // K, V, dK, dV
   const float c2 = alpha * kLog2e;
-
-  // Q_i / dO_i tiles go global -> LDS asynchronously; L_i (pre-multiplied by log2 e) and -delta_i
-  // (64 floats each) pass through one register of threads 0..127.  The dP accumulator starts
-  // from -delta, so that the matrix instructions deliver dP - delta directly (Alg. 2 step 12).
-  float sreg = 0.f;
-  TileLoader<D> loader;
-  loader.init(tid, sn);
   FragOffsets<D> fo;
   init_frag_offsets<D>(fo, lane);
-  // Current query head: its first element in Q / dO and in LSE / delta.  With GROUPED the
-  // work-group moves on to the next head of its group (at distance lay.sh and N) after tile
-  // nt - 1, without breaking the double buffering: `step` counts tiles over all heads.
-  const bf16_t* Qh = Q + head_base(lay, bq0);
-  const bf16_t* dOh = dO + head_base(lay, bq0);
-  const float* Lh = LSE + (size_t)bq0 * N;
-  const float* Dh = delta + (size_t)bq0 * N;
-  const int total = group * (nt - t0);
-  auto load_tile = [&](const bf16_t* Qp, const bf16_t* dOp, const float* Lp, const float* Dp, int t, int buf) {
-    loader.template load_rows<RAGGED>(ldsQ + buf * TILE_BYTES, Qp, t * kQTile, N, tid);
-    loader.template load_rows<RAGGED>(ldsdO + buf * TILE_BYTES, dOp, t * kQTile, N, tid);
-    const int row = t * kQTile + (tid & (kQTile - 1));
-    const int rowc = (RAGGED && row >= N) ? N - 1 : row;
-    if (tid < kQTile) sreg = Lp[rowc] * kLog2e;
-    else if (tid < 2 * kQTile) sreg = -Dp[rowc];   // LDS holds -delta
-  };
-  auto store_stats = [&](int buf) {
-    if (tid < kQTile) ldsL[buf * kQTile + tid] = sreg;
-    else if (tid < 2 * kQTile) ldsD[buf * kQTile + tid - kQTile] = sreg;
-  };
-  load_tile(Qh, dOh, Lh, Dh, t0, 0);
-  store_stats(0);
-  wait_vmem();
-  __syncthreads();
+  TileLoader<D> loader;
+  loader.init(tid, sn);
 
-  // One query tile; BUF (which LDS buffer holds it) is a compile-time constant so that every LDS
-  // address is a precomputed per-lane offset plus an immediate.
-  auto tile_step = [&](auto buf_c, int t, int step) {
-    constexpr int buf = decltype(buf_c)::value;
-    const bool has_next = (step + 1 < total);
-    if (has_next) {
-      if (GROUPED && t + 1 == nt) {   // on to the next query head of the group
-        Qh += lay.sh; dOh += lay.sh; Lh += N; Dh += N;
-        load_tile(Qh, dOh, Lh, Dh, t0, buf ^ 1);
-      } else {
-        load_tile(Qh, dOh, Lh, Dh, t + 1, buf ^ 1);
-      }
+  for (int part = 0; part < (CAUSAL ? 2 : 1); ++part) {
+    const int kt = (part == 0) ? kt_first : nkt - 1 - kt_first;
+    if (part == 1 && kt == kt_first) break;            // odd number of blocks: the middle one has no partner
+    const int k0 = kt * kKeysPerWG;
+    const int kw = k0 + 32 * wave;
+
+    // K_j^T / V_j^T fragments (B operands): lane (r,h) holds K[kw + r][16kc + 8h .. +7]
+    // (keys past the sequence end read the last row; their gradients are not stored)
+    const int keyc = (RAGGED && kw + r >= N) ? N - 1 : kw + r;
+    bf16x8 kf[D / 16], vf[D / 16];
+#pragma unroll
+    for (int kc = 0; kc < D / 16; ++kc) {
+      kf[kc] = *reinterpret_cast<const bf16x8*>(K + head_off + (size_t)keyc * sn + 16 * kc + 8 * h);
+      vf[kc] = *reinterpret_cast<const bf16x8*>(V + head_off + (size_t)keyc * sn + 16 * kc + 8 * h);
     }
-    const char* tQ = smem + buf * TILE_BYTES;
-    const char* tdO = smem + (2 + buf) * TILE_BYTES;
-    const float* tL = reinterpret_cast<const float*>(smem + 4 * TILE_BYTES) + buf * kQTile;
-    const float* tD = reinterpret_cast<const float*>(smem + 4 * TILE_BYTES) + 2 * kQTile + buf * kQTile;
-    const int qt0 = t * kQTile;
-    // one 32-query block against this wave's 32 keys; DIAG: the block crosses the diagonal
-    auto qblock = [&](auto diag_c, int qb) {
-      constexpr bool DIAG = decltype(diag_c)::value;
-      const int qb0 = qt0 + 32 * qb;
-      const bool tail = RAGGED && qb0 + 32 > N;              // some query rows lie past the sequence end
-      // ---- S = Q_i K_j^T and dP = dO_i V_j^T (Alg. 2 steps 8, 11); rows = queries, lane = key
-      f32x16 s, dp;
+    f32x16 dVt[D / 32], dKt[D / 32];
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(tD + 32 * qb + 8 * g + 4 * h);
+    for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { s[4 * g + e] = 0.f; dp[4 * g + e] = d4[e]; }
-      }
-#pragma unroll
-      for (int kc = 0; kc < D / 16; ++kc) {
-        s = mfma32(lds_row8<D>(tQ, fo, 32 * qb, kc), kf[kc], s);
-        dp = mfma32(lds_row8<D>(tdO, fo, 32 * qb, kc), vf[kc], dp);
-      }
-      sched_reads_ahead_of_mfma<D / 8, 1, 4>();
-      if (tail) {   // rows past the sequence end: P = exp(-inf) = 0, so they add nothing to dK, dV
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-          if (qb0 + 8 * (i >> 2) + 4 * h + (i & 3) >= N) s[i] = -INFINITY;
-      }
-      // ---- P = exp(S - L) (step 9), dS = P o (dP - delta) (step 12)
-      bf16x8 pf[2], dsf[2];
-      const int key = kw + r;
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const f32x4 l4 = *reinterpret_cast<const f32x4*>(tL + 32 * qb + 8 * g + 4 * h);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = 4 * g + e;
-          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l4[e]));
-          if (DIAG) {
-            int q = qb0 + 8 * g + 4 * h + e;
-            if (key > q) p = 0.f;
-          }
-          float ds = p * dp[i];                     // dp already holds dP - delta
-          pf[i >> 3][i & 7] = (bf16_t)p;
-          dsf[i >> 3][i & 7] = (bf16_t)ds;
-        }
-      }
-      // ---- dV_j^T += dO_i^T P ,  dK_j^T += Q_i^T dS  (steps 10, 14)
-#pragma unroll
-      for (int cc = 0; cc < 2; ++cc)
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db) {
-          dVt[db] = mfma32(lds_col8<D>(tdO, fo, 32 * qb + 16 * cc, db), pf[cc], dVt[db]);
-          dKt[db] = mfma32(lds_col8<D>(tQ, fo, 32 * qb + 16 * cc, db), dsf[cc], dKt[db]);
-        }
-      sched_reads_ahead_of_mfma<D / 8, 2, 4>();
+      for (int i = 0; i < 16; ++i) { dVt[db][i] = 0.f; dKt[db][i] = 0.f; }
+
+    const int t0 = CAUSAL ? k0 / kQTile : 0;         // first query tile that sees any key of this block
+    const int nt = RAGGED ? (N + kQTile - 1) / kQTile : N / kQTile;
+
+    // Q_i / dO_i tiles go global -> LDS asynchronously; L_i (pre-multiplied by log2 e) and -delta_i
+    // (64 floats each) pass through one register of threads 0..127.  The dP accumulator starts
+    // from -delta, so that the matrix instructions deliver dP - delta directly (Alg. 2 step 12).
+    float sreg = 0.f;
+    // Current query head: its first element in Q / dO and in LSE / delta.  With GROUPED the
+    // work-group moves on to the next head of its group (at distance lay.sh and N) after tile
+    // nt - 1, without breaking the double buffering: `step` counts tiles over all heads.
+    const bf16_t* Qh = Q + head_base(lay, bq0);
+    const bf16_t* dOh = dO + head_base(lay, bq0);
+    const float* Lh = LSE + (size_t)bq0 * N;
+    const float* Dh = delta + (size_t)bq0 * N;
+    const int total = group * (nt - t0);
+    auto load_tile = [&](const bf16_t* Qp, const bf16_t* dOp, const float* Lp, const float* Dp, int t, int buf) {
+      loader.template load_rows<RAGGED>(ldsQ + buf * TILE_BYTES, Qp, t * kQTile, N, tid);
+      loader.template load_rows<RAGGED>(ldsdO + buf * TILE_BYTES, dOp, t * kQTile, N, tid);
+      const int row = t * kQTile + (tid & (kQTile - 1));
+      const int rowc = (RAGGED && row >= N) ? N - 1 : row;
+      if (tid < kQTile) sreg = Lp[rowc] * kLog2e;
+      else if (tid < 2 * kQTile) sreg = -Dp[rowc];   // LDS holds -delta
     };
-    // Both 32-query blocks of a tile that lies entirely below the diagonal for this wave, as one
-    // software-pipelined sequence of 4 x NS "slots" (one matrix instruction each).  The phase
-    // order is fixed by hand (scheduling fences between the phases and between the slots of the
-    // two pure matrix phases; inside the mixed phases the compiler interleaves):
-    //   phase 1  S,dP of block 0
-    //   phase 2  S,dP of block 1        | vector work of block 0 (P, dS), one element per slot
-    //   phase 3  dV,dK += block 0       | vector work of block 1
-    //   phase 4  dV,dK += block 1
-    // and every LDS fragment read is issued AH slots before the matrix instruction that uses it.
-    auto tile_pipelined = [&]() {
-      constexpr int NS = D / 8;            // slots per phase
-      constexpr int AH = (D >= 128) ? 8 : 4;  // LDS read-ahead, in slots
-      constexpr int R = 2 * AH;            // fragment ring size (> AH)
-      constexpr int EPS = 16 / NS;         // score elements handled per slot
-      bf16x8 ring[R];
-      // slot s of an S/dP phase: kc = s/2, even -> S (Q_i, K_j), odd -> dP (dO_i, V_j)
-      auto rd_sdp = [&](int qb, int sl) -> bf16x8 {
-        return lds_row8<D>((sl & 1) ? tdO : tQ, fo, 32 * qb, sl >> 1);
-      };
-      // slot s of a dV/dK phase: cc = s / (2 D/32), db = (s/2) % (D/32), even -> dV (dO_i^T), odd -> dK (Q_i^T)
-      auto rd_dvdk = [&](int qb, int sl) -> bf16x8 {
-        return lds_col8<D>((sl & 1) ? tQ : tdO, fo, 32 * qb + 16 * (sl / (2 * (D / 32))),
-                           (sl >> 1) % (D / 32));
-      };
-      f32x16 s0, dp0, s1, dp1;
-      bf16x8 pf0[2], dsf0[2], pf1[2], dsf1[2];
-      f32x4 lq0[4], lq1[4];                        // L_i log2e of the 16 rows a lane sees
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {                // the dP accumulators start from -delta_i
-        lq0[g] = *reinterpret_cast<const f32x4*>(tL + 8 * g + 4 * h);
-        const f32x4 d0 = *reinterpret_cast<const f32x4*>(tD + 8 * g + 4 * h);
-        const f32x4 d1 = *reinterpret_cast<const f32x4*>(tD + 32 + 8 * g + 4 * h);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          s0[4 * g + e] = 0.f; s1[4 * g + e] = 0.f;
-          dp0[4 * g + e] = d0[e]; dp1[4 * g + e] = d1[e];
-        }
-      }
-#pragma unroll
-      for (int a = 0; a < AH; ++a) ring[a] = rd_sdp(0, a);
-      __builtin_amdgcn_sched_barrier(0);
-      // ---- phase 1
-#pragma unroll
-      for (int sl = 0; sl < NS; ++sl) {
-        ring[(sl + AH) % R] = (sl + AH < NS) ? rd_sdp(0, sl + AH) : rd_sdp(1, sl + AH - NS);
-        if (sl & 1) dp0 = mfma32(ring[sl % R], vf[sl >> 1], dp0);
-        else s0 = mfma32(ring[sl % R], kf[sl >> 1], s0);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-#pragma unroll
-      for (int g = 0; g < 4; ++g) lq1[g] = *reinterpret_cast<const f32x4*>(tL + 32 + 8 * g + 4 * h);
-      // ---- phase 2
-#pragma unroll
-      for (int sl = 0; sl < NS; ++sl) {
-        ring[(NS + sl + AH) % R] = (sl + AH < NS) ? rd_sdp(1, sl + AH) : rd_dvdk(0, sl + AH - NS);
-        if (sl & 1) dp1 = mfma32(ring[(NS + sl) % R], vf[sl >> 1], dp1);
-        else s1 = mfma32(ring[(NS + sl) % R], kf[sl >> 1], s1);
-#pragma unroll
-        for (int e = 0; e < EPS; ++e) {
-          const int i = sl * EPS + e;
-          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[i], c2, -lq0[i >> 2][i & 3]));
-          float ds = p * dp0[i];
-          pf0[i >> 3][i & 7] = (bf16_t)p;
-          dsf0[i >> 3][i & 7] = (bf16_t)ds;
-        }
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      // ---- phase 3
-#pragma unroll
-      for (int sl = 0; sl < NS; ++sl) {
-        ring[(2 * NS + sl + AH) % R] = (sl + AH < NS) ? rd_dvdk(0, sl + AH) : rd_dvdk(1, sl + AH - NS);
-        const int cc = sl / (2 * (D / 32)), db = (sl >> 1) % (D / 32);
-        if (sl & 1) dKt[db] = mfma32(ring[(2 * NS + sl) % R], dsf0[cc], dKt[db]);
-        else dVt[db] = mfma32(ring[(2 * NS + sl) % R], pf0[cc], dVt[db]);
-#pragma unroll
-        for (int e = 0; e < EPS; ++e) {
-          const int i = sl * EPS + e;
-          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[i], c2, -lq1[i >> 2][i & 3]));
-          float ds = p * dp1[i];
-          pf1[i >> 3][i & 7] = (bf16_t)p;
-          dsf1[i >> 3][i & 7] = (bf16_t)ds;
-        }
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      // ---- phase 4
-#pragma unroll
-      for (int sl = 0; sl < NS; ++sl) {
-        if (sl + AH < NS) ring[(3 * NS + sl + AH) % R] = rd_dvdk(1, sl + AH);
-        const int cc = sl / (2 * (D / 32)), db = (sl >> 1) % (D / 32);
-        if (sl & 1) dKt[db] = mfma32(ring[(3 * NS + sl) % R], dsf1[cc], dKt[db]);
-        else dVt[db] = mfma32(ring[(3 * NS + sl) % R], pf1[cc], dVt[db]);
-        __builtin_amdgcn_sched_barrier(0);
-      }
+    auto store_stats = [&](int buf) {
+      if (tid < kQTile) ldsL[buf * kQTile + tid] = sreg;
+      else if (tid < 2 * kQTile) ldsD[buf * kQTile + tid - kQTile] = sreg;
     };
-    if ((!CAUSAL || qt0 >= kw + 31) && (!RAGGED || qt0 + kQTile <= N)) {
-      tile_pipelined();
-    } else {
-#pragma unroll
-      for (int qb = 0; qb < kQTile / 32; ++qb) {
-        const int qb0 = qt0 + 32 * qb;
-        if (CAUSAL && qb0 + 31 < kw) continue;     // every query of the block precedes every key of the wave
-        if (RAGGED && qb0 >= N) continue;                    // nothing but padding
-        if (CAUSAL && qb0 < kw + 31) qblock(std::true_type{}, qb);
-        else qblock(std::false_type{}, qb);
-      }
-    }
-    if (has_next) store_stats(buf ^ 1);
+    load_tile(Qh, dOh, Lh, Dh, t0, 0);
+    store_stats(0);
     wait_vmem();
     __syncthreads();
-  };
-  if (!GROUPED) {
-    for (int t = t0; t < nt; t += 2) {
-      tile_step(std::integral_constant<int, 0>{}, t, t - t0);
-      if (t + 1 < nt) tile_step(std::integral_constant<int, 1>{}, t + 1, t + 1 - t0);
-    }
-  } else {
-    int t = t0;
-    for (int step = 0; step < total; step += 2) {
-      tile_step(std::integral_constant<int, 0>{}, t, step);
-      t = (t + 1 == nt) ? t0 : t + 1;
-      if (step + 1 < total) {
-        tile_step(std::integral_constant<int, 1>{}, t, step + 1);
+
+    // One query tile; BUF (which LDS buffer holds it) is a compile-time constant so that every LDS
+    // address is a precomputed per-lane offset plus an immediate.
+    auto tile_step = [&](auto buf_c, int t, int step) {
+      constexpr int buf = decltype(buf_c)::value;
+      const bool has_next = (step + 1 < total);
+      if (has_next) {
+        if (GROUPED && t + 1 == nt) {   // on to the next query head of the group
+          Qh += lay.sh; dOh += lay.sh; Lh += N; Dh += N;
+          load_tile(Qh, dOh, Lh, Dh, t0, buf ^ 1);
+        } else {
+          load_tile(Qh, dOh, Lh, Dh, t + 1, buf ^ 1);
+        }
+      }
+      const char* tQ = smem + buf * TILE_BYTES;
+      const char* tdO = smem + (2 + buf) * TILE_BYTES;
+      const float* tL = reinterpret_cast<const float*>(smem + 4 * TILE_BYTES) + buf * kQTile;
+      const float* tD = reinterpret_cast<const float*>(smem + 4 * TILE_BYTES) + 2 * kQTile + buf * kQTile;
+      const int qt0 = t * kQTile;
+      // one 32-query block against this wave's 32 keys; DIAG: the block crosses the diagonal
+      auto qblock = [&](auto diag_c, int qb) {
+        constexpr bool DIAG = decltype(diag_c)::value;
+        const int qb0 = qt0 + 32 * qb;
+        const bool tail = RAGGED && qb0 + 32 > N;              // some query rows lie past the sequence end
+        // ---- S = Q_i K_j^T and dP = dO_i V_j^T (Alg. 2 steps 8, 11); rows = queries, lane = key
+        f32x16 s, dp;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(tD + 32 * qb + 8 * g + 4 * h);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { s[4 * g + e] = 0.f; dp[4 * g + e] = d4[e]; }
+        }
+#pragma unroll
+        for (int kc = 0; kc < D / 16; ++kc) {
+          s = mfma32(lds_row8<D>(tQ, fo, 32 * qb, kc), kf[kc], s);
+          dp = mfma32(lds_row8<D>(tdO, fo, 32 * qb, kc), vf[kc], dp);
+        }
+        sched_reads_ahead_of_mfma<D / 8, 1, 4>();
+        if (tail) {   // rows past the sequence end: P = exp(-inf) = 0, so they add nothing to dK, dV
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            if (qb0 + 8 * (i >> 2) + 4 * h + (i & 3) >= N) s[i] = -INFINITY;
+        }
+        // ---- P = exp(S - L) (step 9), dS = P o (dP - delta) (step 12)
+        bf16x8 pf[2], dsf[2];
+        const int key = kw + r;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(tL + 32 * qb + 8 * g + 4 * h);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int i = 4 * g + e;
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l4[e]));
+            if (DIAG) {
+              int q = qb0 + 8 * g + 4 * h + e;
+              if (key > q) p = 0.f;
+            }
+            float ds = p * dp[i];                     // dp already holds dP - delta
+            pf[i >> 3][i & 7] = (bf16_t)p;
+            dsf[i >> 3][i & 7] = (bf16_t)ds;
+          }
+        }
+        // ---- dV_j^T += dO_i^T P ,  dK_j^T += Q_i^T dS  (steps 10, 14)
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db) {
+            dVt[db] = mfma32(lds_col8<D>(tdO, fo, 32 * qb + 16 * cc, db), pf[cc], dVt[db]);
+            dKt[db] = mfma32(lds_col8<D>(tQ, fo, 32 * qb + 16 * cc, db), dsf[cc], dKt[db]);
+          }
+        sched_reads_ahead_of_mfma<D / 8, 2, 4>();
+      };
+      // Both 32-query blocks of a tile that lies entirely below the diagonal for this wave, as one
+      // software-pipelined sequence of 4 x NS "slots" (one matrix instruction each).  The phase
+      // order is fixed by hand (scheduling fences between the phases and between the slots of the
+      // two pure matrix phases; inside the mixed phases the compiler interleaves):
+      //   phase 1  S,dP of block 0
+      //   phase 2  S,dP of block 1        | vector work of block 0 (P, dS), one element per slot
+      //   phase 3  dV,dK += block 0       | vector work of block 1
+      //   phase 4  dV,dK += block 1
+      // and every LDS fragment read is issued AH slots before the matrix instruction that uses it.
+      auto tile_pipelined = [&]() {
+        constexpr int NS = D / 8;            // slots per phase
+        constexpr int AH = (D >= 128) ? 8 : 4;  // LDS read-ahead, in slots
+        constexpr int R = 2 * AH;            // fragment ring size (> AH)
+        constexpr int EPS = 16 / NS;         // score elements handled per slot
+        bf16x8 ring[R];
+        // slot s of an S/dP phase: kc = s/2, even -> S (Q_i, K_j), odd -> dP (dO_i, V_j)
+        auto rd_sdp = [&](int qb, int sl) -> bf16x8 {
+          return lds_row8<D>((sl & 1) ? tdO : tQ, fo, 32 * qb, sl >> 1);
+        };
+        // slot s of a dV/dK phase: cc = s / (2 D/32), db = (s/2) % (D/32), even -> dV (dO_i^T), odd -> dK (Q_i^T)
+        auto rd_dvdk = [&](int qb, int sl) -> bf16x8 {
+          return lds_col8<D>((sl & 1) ? tQ : tdO, fo, 32 * qb + 16 * (sl / (2 * (D / 32))),
+                             (sl >> 1) % (D / 32));
+        };
+        f32x16 s0, dp0, s1, dp1;
+        bf16x8 pf0[2], dsf0[2], pf1[2], dsf1[2];
+        f32x4 lq0[4], lq1[4];                        // L_i log2e of the 16 rows a lane sees
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {                // the dP accumulators start from -delta_i
+          lq0[g] = *reinterpret_cast<const f32x4*>(tL + 8 * g + 4 * h);
+          const f32x4 d0 = *reinterpret_cast<const f32x4*>(tD + 8 * g + 4 * h);
+          const f32x4 d1 = *reinterpret_cast<const f32x4*>(tD + 32 + 8 * g + 4 * h);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            s0[4 * g + e] = 0.f; s1[4 * g + e] = 0.f;
+            dp0[4 * g + e] = d0[e]; dp1[4 * g + e] = d1[e];
+          }
+        }
+#pragma unroll
+        for (int a = 0; a < AH; ++a) ring[a] = rd_sdp(0, a);
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- phase 1
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) {
+          ring[(sl + AH) % R] = (sl + AH < NS) ? rd_sdp(0, sl + AH) : rd_sdp(1, sl + AH - NS);
+          if (sl & 1) dp0 = mfma32(ring[sl % R], vf[sl >> 1], dp0);
+          else s0 = mfma32(ring[sl % R], kf[sl >> 1], s0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) lq1[g] = *reinterpret_cast<const f32x4*>(tL + 32 + 8 * g + 4 * h);
+        // ---- phase 2
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) {
+          ring[(NS + sl + AH) % R] = (sl + AH < NS) ? rd_sdp(1, sl + AH) : rd_dvdk(0, sl + AH - NS);
+          if (sl & 1) dp1 = mfma32(ring[(NS + sl) % R], vf[sl >> 1], dp1);
+          else s1 = mfma32(ring[(NS + sl) % R], kf[sl >> 1], s1);
+#pragma unroll
+          for (int e = 0; e < EPS; ++e) {
+            const int i = sl * EPS + e;
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[i], c2, -lq0[i >> 2][i & 3]));
+            float ds = p * dp0[i];
+            pf0[i >> 3][i & 7] = (bf16_t)p;
+            dsf0[i >> 3][i & 7] = (bf16_t)ds;
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- phase 3
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) {
+          ring[(2 * NS + sl + AH) % R] = (sl + AH < NS) ? rd_dvdk(0, sl + AH) : rd_dvdk(1, sl + AH - NS);
+          const int cc = sl / (2 * (D / 32)), db = (sl >> 1) % (D / 32);
+          if (sl & 1) dKt[db] = mfma32(ring[(2 * NS + sl) % R], dsf0[cc], dKt[db]);
+          else dVt[db] = mfma32(ring[(2 * NS + sl) % R], pf0[cc], dVt[db]);
+#pragma unroll
+          for (int e = 0; e < EPS; ++e) {
+            const int i = sl * EPS + e;
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[i], c2, -lq1[i >> 2][i & 3]));
+            float ds = p * dp1[i];
+            pf1[i >> 3][i & 7] = (bf16_t)p;
+            dsf1[i >> 3][i & 7] = (bf16_t)ds;
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- phase 4
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) {
+          if (sl + AH < NS) ring[(3 * NS + sl + AH) % R] = rd_dvdk(1, sl + AH);
+          const int cc = sl / (2 * (D / 32)), db = (sl >> 1) % (D / 32);
+          if (sl & 1) dKt[db] = mfma32(ring[(3 * NS + sl) % R], dsf1[cc], dKt[db]);
+          else dVt[db] = mfma32(ring[(3 * NS + sl) % R], pf1[cc], dVt[db]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      };
+      if ((!CAUSAL || qt0 >= kw + 31) && (!RAGGED || qt0 + kQTile <= N)) {
+        tile_pipelined();
+      } else {
+#pragma unroll
+        for (int qb = 0; qb < kQTile / 32; ++qb) {
+          const int qb0 = qt0 + 32 * qb;
+          if (CAUSAL && qb0 + 31 < kw) continue;     // every query of the block precedes every key of the wave
+          if (RAGGED && qb0 >= N) continue;                    // nothing but padding
+          if (CAUSAL && qb0 < kw + 31) qblock(std::true_type{}, qb);
+          else qblock(std::false_type{}, qb);
+        }
+      }
+      if (has_next) store_stats(buf ^ 1);
+      wait_vmem();
+      __syncthreads();
+    };
+    if (!GROUPED) {
+      for (int t = t0; t < nt; t += 2) {
+        tile_step(std::integral_constant<int, 0>{}, t, t - t0);
+        if (t + 1 < nt) tile_step(std::integral_constant<int, 1>{}, t + 1, t + 1 - t0);
+      }
+    } else {
+      int t = t0;
+      for (int step = 0; step < total; step += 2) {
+        tile_step(std::integral_constant<int, 0>{}, t, step);
         t = (t + 1 == nt) ? t0 : t + 1;
+        if (step + 1 < total) {
+          tile_step(std::integral_constant<int, 1>{}, t, step + 1);
+          t = (t + 1 == nt) ? t0 : t + 1;
+        }
       }
     }
-  }
-  if (!RAGGED || kw + r < N) {
-    store_acc_T<D>(dV + head_off + (size_t)(kw + r) * sn, dVt, 1.0f, h);
-    store_acc_T<D>(dK + head_off + (size_t)(kw + r) * sn, dKt, alpha, h);
+    if (!RAGGED || kw + r < N) {
+      store_acc_T<D>(dV + head_off + (size_t)(kw + r) * sn, dVt, 1.0f, h);
+      store_acc_T<D>(dK + head_off + (size_t)(kw + r) * sn, dKt, alpha, h);
+    }
   }
 }
 
@@ -489,7 +497,8 @@ static hipError_t launch_dkdv(const void* Q, const void* K, const void* V, const
   auto k = attn_bwd_dkdv_kernel<D, CAUSAL, RAGGED, GROUPED>;
   hipError_t e;
   if ((e = set_smem(k, smem, set)) != hipSuccess) return e;
-  hipLaunchKernelGGL(k, dim3((BH / lay.group) * ((N + kKeysPerWG - 1) / kKeysPerWG)), dim3(256), smem, st, (const bf16_t*)Q,
+  const int nkt = (N + kKeysPerWG - 1) / kKeysPerWG;
+  hipLaunchKernelGGL(k, dim3((BH / lay.group) * (CAUSAL ? (nkt + 1) / 2 : nkt)), dim3(256), smem, st, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
                      (bf16_t*)dK, (bf16_t*)dV, N, alpha, lay);
   return hipGetLastError();
