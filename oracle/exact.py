@@ -5,7 +5,11 @@ N x N score matrix is materialised, nothing is tiled, fused or reordered.  One
 (batch, head) problem is an N x d triple Q, K, V; the 4-D wrappers loop over heads.
 
 Conventions (the paper is silent on both; the choices are stated, not derived):
-  * causal masking: query row r attends to key columns c <= r;
+  * causal masking: query row r attends to key columns c <= r; when the numbers of queries and
+    keys differ (N_q x d queries against N_k x d keys / values) the mask is aligned at the bottom
+    right, c <= r + (N_k - N_q): the last query sees every key.  A query that sees no key at
+    all (only possible when N_q > N_k) has P = 0, O = 0, L = -inf and takes no part in any
+    gradient;
   * the softmax scale alpha multiplies the scores S = alpha Q K^T, and therefore
     appears once more in dQ and dK (Eq. 2 / Appendix E.2: dS = alpha P o (dP - delta)).
 """
@@ -21,17 +25,19 @@ def scores(Q, K, alpha, causal):
         n_q, n_k = S.shape
         r = np.arange(n_q)[:, None]
         c = np.arange(n_k)[None, :]
-        S = np.where(c > r, -np.inf, S)
+        S = np.where(c > r + (n_k - n_q), -np.inf, S)
     return S
 
 
 def softmax_rows(S):
     """Row softmax and row logsumexp of S, via the safe form exp(S - rowmax S) (Sec. 3.3.2)."""
     m = np.max(S, axis=1, keepdims=True)
-    E = np.exp(S - m)
+    empty = np.isneginf(m)                      # rows with every entry masked
+    E = np.exp(S - np.where(empty, 0.0, m))
     ell = np.sum(E, axis=1, keepdims=True)
-    P = E / ell
-    L = (m + np.log(ell))[:, 0]
+    with np.errstate(divide="ignore", invalid="ignore"):
+        P = np.where(empty, 0.0, E / ell)
+        L = np.where(empty, -np.inf, m + np.log(ell))[:, 0]
     return P, L
 
 
@@ -85,16 +91,17 @@ def forward_backward(Q, K, V, dO, alpha, causal, row_block=None):
     Q = np.asarray(Q, dtype=np.float64); K = np.asarray(K, dtype=np.float64)
     V = np.asarray(V, dtype=np.float64); dO = np.asarray(dO, dtype=np.float64)
     N, d = Q.shape
+    Nk = K.shape[0]
     rb = N if row_block is None else int(row_block)
     O = np.empty((N, d)); L = np.empty(N); delta = np.empty(N)
-    dQ = np.empty((N, d)); dK = np.zeros((N, d)); dV = np.zeros((N, d))
+    dQ = np.empty((N, d)); dK = np.zeros((Nk, d)); dV = np.zeros((Nk, d))
     for r0 in range(0, N, rb):
         r1 = min(N, r0 + rb)
         S = alpha * (Q[r0:r1] @ K.T)
         if causal:
             r = np.arange(r0, r1)[:, None]
-            c = np.arange(N)[None, :]
-            S = np.where(c > r, -np.inf, S)
+            c = np.arange(Nk)[None, :]
+            S = np.where(c > r + (Nk - N), -np.inf, S)
         P, L[r0:r1] = softmax_rows(S)
         O[r0:r1] = P @ V
         delta[r0:r1] = np.sum(dO[r0:r1] * O[r0:r1], axis=1)

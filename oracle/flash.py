@@ -58,13 +58,14 @@ FP64 = Precision("fp64", np.float64, lambda x: x)
 BF16 = Precision("bf16", np.float32, round_to_bf16)
 
 
-def _tile_scores(Qw, Kj, alpha, causal, k0, prec):
-    """alpha Q K_j^T for key tile starting at column k0 (Alg. 1 step 6), masked entries -inf."""
+def _tile_scores(Qw, Kj, alpha, causal, k0, prec, shift=0):
+    """alpha Q K_j^T for key tile starting at column k0 (Alg. 1 step 6), masked entries -inf.
+    shift = N_k - N_q: the causal mask is aligned at the bottom right (see oracle.exact)."""
     S = (Qw @ Kj.T) * prec.dtype(alpha)
     if causal:
         r = np.arange(Qw.shape[0])[:, None]
         c = (k0 + np.arange(Kj.shape[0]))[None, :]
-        S = np.where(c > r, prec.dtype(-np.inf), S)
+        S = np.where(c > r + shift, prec.dtype(-np.inf), S)
     return S.astype(prec.dtype)
 
 
@@ -100,7 +101,7 @@ def forward(Q, K, V, alpha, causal, variant=STANDARD, beta=2.0, eps=1e-3, Bc=Non
     with np.errstate(invalid="ignore", over="ignore", divide="ignore"):
         for k0 in range(0, Nk, Bc):            # Alg. 1 step 5
             Kj = Kw[k0:k0 + Bc]; Vj = Vw[k0:k0 + Bc]
-            S = _tile_scores(Qw, Kj, alpha, causal, k0, prec)            # step 6
+            S = _tile_scores(Qw, Kj, alpha, causal, k0, prec, Nk - N)    # step 6
             r_m = np.max(S, axis=1)                                       # Alg. 3: tile row max
             m_prime = r_m
             if variant == MITIGATED:
@@ -122,8 +123,9 @@ def forward(Q, K, V, alpha, causal, variant=STANDARD, beta=2.0, eps=1e-3, Bc=Non
             ones += np.sum(Phat == dt(1.0), axis=1)
             m = m_new
         Obar = prec.rnd(acc).astype(dt) if round_obar else acc            # (r3)
-        O = prec.rnd(Obar / ell[:, None]).astype(dt)                       # step 10, (r4)
-        Ohp = (acc / ell[:, None]).astype(dt)
+        seen = ~np.isneginf(m)[:, None]       # a query with no visible key (N_q > N_k) outputs 0, L = -inf
+        O = np.where(seen, prec.rnd(Obar / ell[:, None]), dt(0.0)).astype(dt)   # step 10, (r4)
+        Ohp = np.where(seen, acc / ell[:, None], dt(0.0)).astype(dt)
         L = (m + np.log(ell)).astype(dt)                                   # step 11
     return {"O": O, "L": L, "Obar": Obar, "Oacc": acc, "ell": ell, "m": m,
             "fired": fired, "ones": ones, "Ohp": Ohp}
@@ -142,14 +144,16 @@ def backward(Q, K, V, O, dO, L, alpha, causal, Bc=None, Br=None, prec=BF16):
     Qw = np.asarray(Q, dtype=dt); Kw = np.asarray(K, dtype=dt); Vw = np.asarray(V, dtype=dt)
     Ow = np.asarray(O, dtype=dt); dOw = np.asarray(dO, dtype=dt); Lw = np.asarray(L, dtype=dt)
     N, d = Qw.shape
-    Bc = N if Bc is None else int(Bc)
+    Nk = Kw.shape[0]
+    Bc = Nk if Bc is None else int(Bc)
     Br = N if Br is None else int(Br)
+    Lw = np.where(np.isneginf(Lw), dt(0.0), Lw)     # queries that see no key: every score is -inf, P = 0
     delta = np.sum(dOw * Ow, axis=1, dtype=dt)                            # Alg. 2 step 4
     dQ = np.zeros((N, d), dtype=dt)                                       # step 3
-    dK = np.zeros((N, d), dtype=dt)
-    dV = np.zeros((N, d), dtype=dt)
+    dK = np.zeros((Nk, d), dtype=dt)
+    dV = np.zeros((Nk, d), dtype=dt)
     with np.errstate(invalid="ignore", over="ignore"):
-        for k0 in range(0, N, Bc):                                        # step 5
+        for k0 in range(0, Nk, Bc):                                       # step 5
             Kj = Kw[k0:k0 + Bc]; Vj = Vw[k0:k0 + Bc]
             for q0 in range(0, N, Br):                                    # step 7
                 Qi = Qw[q0:q0 + Br]; dOi = dOw[q0:q0 + Br]
@@ -157,7 +161,7 @@ def backward(Q, K, V, O, dO, L, alpha, causal, Bc=None, Br=None, prec=BF16):
                 if causal:
                     r = (q0 + np.arange(Qi.shape[0]))[:, None]
                     c = (k0 + np.arange(Kj.shape[0]))[None, :]
-                    S = np.where(c > r, dt(-np.inf), S)
+                    S = np.where(c > r + (Nk - N), dt(-np.inf), S)
                 P = np.exp(S.astype(dt) - Lw[q0:q0 + Br, None]).astype(dt)   # step 9
                 dV[k0:k0 + Bc] += prec.rnd(P).astype(dt).T @ dOi          # step 10
                 dP = (dOi @ Vj.T).astype(dt)                              # step 11
@@ -179,12 +183,14 @@ def delta_recomputed(Q, K, V, dO, L, alpha, causal, Bc=None, prec=BF16):
     Qw = np.asarray(Q, dtype=dt); Kw = np.asarray(K, dtype=dt); Vw = np.asarray(V, dtype=dt)
     dOw = np.asarray(dO, dtype=dt); Lw = np.asarray(L, dtype=dt)
     N = Qw.shape[0]
-    Bc = N if Bc is None else int(Bc)
+    Nk = Kw.shape[0]
+    Bc = Nk if Bc is None else int(Bc)
+    Lw = np.where(np.isneginf(Lw), dt(0.0), Lw)
     delta = np.zeros(N, dtype=dt)
     with np.errstate(invalid="ignore", over="ignore"):
-        for k0 in range(0, N, Bc):
+        for k0 in range(0, Nk, Bc):
             Kj = Kw[k0:k0 + Bc]; Vj = Vw[k0:k0 + Bc]
-            S = _tile_scores(Qw, Kj, alpha, causal, k0, prec)
+            S = _tile_scores(Qw, Kj, alpha, causal, k0, prec, Nk - N)
             P = np.exp(S - Lw[:, None]).astype(dt)
             dP = (dOw @ Vj.T).astype(dt)
             delta = (delta + np.sum(P * dP, axis=1, dtype=dt)).astype(dt)
