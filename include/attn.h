@@ -220,6 +220,27 @@ int attn_bwd_gqa(const void* Q, const void* K, const void* V, const void* O, con
                  int B, int H, int H_kv, int N, int d, int causal, float softmax_scale, int variant,
                  void* stream);
 
+/*
+ * Different numbers of queries and keys: Q, O, dO, dQ are [B,H,Nq,d], K, V, dK, dV are
+ * [B,H,Nk,d] (contiguous), LSE and the workspace's delta are [B,H,Nq]; the workspace size is
+ * attn_bwd_workspace_bytes(B, H, Nq, d).  The algorithms are those of attn_fwd_ex / attn_bwd
+ * (Alg. 1 / 3 and Alg. 2 are written for any pair of lengths).  The paper does not say how a
+ * causal mask is placed on a rectangular score matrix; it is aligned at the bottom right here:
+ * query r sees keys c <= r + (Nk - Nq), so that the last query sees every key (Nq < Nk is a
+ * chunk of queries at the end of a longer sequence).  With Nq > Nk the first Nq - Nk queries see
+ * no key at all: their rows of O and dQ are 0, their LSE is -infinity, and they add nothing to
+ * dK, dV.  Nq == Nk is exactly attn_fwd_ex / attn_bwd.  Nq, Nk >= 1; same checks and error codes
+ * otherwise.
+ */
+int attn_fwd_rect(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                  int B, int H, int Nq, int Nk, int d, int causal, float softmax_scale, int variant,
+                  float beta, float eps, void* stream);
+int attn_bwd_rect(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                  const float* LSE, void* dQ, void* dK, void* dV,
+                  void* workspace, size_t workspace_bytes,
+                  int B, int H, int Nq, int Nk, int d, int causal, float softmax_scale, int variant,
+                  void* stream);
+
 /* Human-readable name of an attn_status (static storage, never NULL). */
 const char* attn_status_string(int status);
 

@@ -5,7 +5,8 @@ pass attn_bwd / attn_bwd_strided of the library (Alg. 1 or Alg. 3 forward, Alg. 
 arXiv 2510.04212); nothing is computed here.  q, k, v are bfloat16 CUDA tensors of logical
 shape [B, H, N, d]; they may be contiguous or share any batch / head / row strides with a
 contiguous last dimension (for instance `x.view(B, N, H, d).permute(0, 2, 1, 3)`), in which case
-no copy is made.  k and v may have fewer heads than q (grouped-query attention).
+no copy is made.  k and v may have fewer heads than q (grouped-query attention), or a different
+sequence length (the causal mask is then aligned at the bottom right).
 """
 import math
 
@@ -28,6 +29,12 @@ class _FlashAttention(torch.autograd.Function):
             ctx.save_for_backward(q, k, v, o, lse)
             ctx.args = (causal, softmax_scale, variant, "gqa")
             return o
+        if k.shape[2] != q.shape[2]:        # different numbers of queries and keys
+            q, k, v = q.contiguous(), k.contiguous(), v.contiguous()
+            o, lse = binding.attn_fwd_rect(q, k, v, causal, softmax_scale, variant, beta, eps)
+            ctx.save_for_backward(q, k, v, o, lse)
+            ctx.args = (causal, softmax_scale, variant, "rect")
+            return o
         strided = not (q.is_contiguous() and k.is_contiguous() and v.is_contiguous())
         if strided and not (_same_layout(q, k, v) and q.stride(3) == 1):
             q, k, v = q.contiguous(), k.contiguous(), v.contiguous()
@@ -46,6 +53,8 @@ class _FlashAttention(torch.autograd.Function):
         causal, softmax_scale, variant, strided = ctx.args
         if strided == "gqa":
             dq, dk, dv = binding.attn_bwd_gqa(q, k, v, o, do.contiguous(), lse, causal, softmax_scale, variant)
+        elif strided == "rect":
+            dq, dk, dv = binding.attn_bwd_rect(q, k, v, o, do.contiguous(), lse, causal, softmax_scale, variant)
         elif strided:
             if do.stride() != q.stride():
                 d2 = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)

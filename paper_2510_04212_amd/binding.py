@@ -47,6 +47,10 @@ _lib.attn_fwd_gqa.argtypes = [_vp] * 5 + [_i, _i, _i, _i, _i, _i, _f, _i, _f, _f
 _lib.attn_fwd_gqa.restype = _i
 _lib.attn_bwd_gqa.argtypes = [_vp] * 9 + [_vp, _sz, _i, _i, _i, _i, _i, _i, _f, _i, _vp]
 _lib.attn_bwd_gqa.restype = _i
+_lib.attn_fwd_rect.argtypes = [_vp] * 5 + [_i, _i, _i, _i, _i, _i, _f, _i, _f, _f, _vp]
+_lib.attn_fwd_rect.restype = _i
+_lib.attn_bwd_rect.argtypes = [_vp] * 9 + [_vp, _sz, _i, _i, _i, _i, _i, _i, _f, _i, _vp]
+_lib.attn_bwd_rect.restype = _i
 _lib.attn_bwd.argtypes = [_vp] * 9 + [_vp, _sz, _i, _i, _i, _i, _i, _f, _i, _vp]
 _lib.attn_bwd.restype = _i
 _lib.attn_bwd_dkdv.argtypes = [_vp] * 8 + [_i, _i, _i, _i, _i, _f, _vp]
@@ -65,7 +69,7 @@ FWD_SINGLE_ROUNDING = 1
 EXPORTS = ["attn_fwd", "attn_fwd_ex", "attn_fwd_opt", "attn_delta", "attn_delta_hp",
            "attn_delta_recompute", "attn_bwd",
            "attn_bwd_dkdv", "attn_bwd_dq", "attn_fwd_strided", "attn_bwd_strided",
-           "attn_fwd_gqa", "attn_bwd_gqa",
+           "attn_fwd_gqa", "attn_bwd_gqa", "attn_fwd_rect", "attn_bwd_rect",
            "attn_bwd_workspace_bytes",
            "attn_status_string", "attn_fwd_key_tile"]
 
@@ -322,4 +326,39 @@ def attn_bwd_gqa(Q, K, V, O, dO, LSE, causal, softmax_scale, variant=STANDARD, w
     _check(_lib.attn_bwd_gqa(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK),
                              _ptr(dV), _ptr(workspace), workspace.numel(), B, H, Hkv, N, d,
                              int(bool(causal)), float(softmax_scale), int(variant), _stream(stream)))
+    return dQ, dK, dV
+
+
+def attn_fwd_rect(Q, K, V, causal, softmax_scale, variant=STANDARD, beta=None, eps=None, stream=None):
+    """Forward with different numbers of queries and keys: Q [B,H,Nq,d], K and V [B,H,Nk,d]
+    (contiguous); the causal mask is aligned at the bottom right."""
+    B, H, Nq, d = _bhnd(Q, "Q")
+    Bk, Hk, Nk, dk = _bhnd(K, "K")
+    if _bhnd(V, "V") != K.shape or (Bk, Hk, dk) != (B, H, d):
+        raise ValueError("K and V must be [B,H,Nk,d] with the batch, heads and head size of Q")
+    O = torch.empty_like(Q)
+    LSE = torch.empty((B, H, Nq), dtype=torch.float32, device=Q.device)
+    _check(_lib.attn_fwd_rect(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), B, H, Nq, Nk, d,
+                              int(bool(causal)), float(softmax_scale), int(variant),
+                              float(DEFAULT_BETA if beta is None else beta),
+                              float(DEFAULT_EPS if eps is None else eps), _stream(stream)))
+    return O, LSE
+
+
+def attn_bwd_rect(Q, K, V, O, dO, LSE, causal, softmax_scale, variant=STANDARD, workspace=None, stream=None):
+    """Backward of attn_fwd_rect: dQ like Q, dK and dV like K."""
+    B, H, Nq, d = _bhnd(Q, "Q")
+    Nk = _bhnd(K, "K")[2]
+    for n, t in (("O", O), ("dO", dO)):
+        if _bhnd(t, n) != (B, H, Nq, d):
+            raise ValueError(f"{n} shape differs from Q")
+    if _bhnd(V, "V") != K.shape or tuple(K.shape) != (B, H, Nk, d):
+        raise ValueError("K and V must be [B,H,Nk,d] with the batch, heads and head size of Q")
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(K)
+    need = bwd_workspace_bytes(B, H, Nq, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Q.device)
+    _check(_lib.attn_bwd_rect(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK),
+                              _ptr(dV), _ptr(workspace), workspace.numel(), B, H, Nq, Nk, d,
+                              int(bool(causal)), float(softmax_scale), int(variant), _stream(stream)))
     return dQ, dK, dV

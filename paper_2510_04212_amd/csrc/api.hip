@@ -12,6 +12,7 @@ struct Layout {
   int H;
   long long sb_kv, sh_kv;   // batch / head strides of K, V, dK, dV
   int group;                // query heads per key/value head
+  int Nk;                   // rows of K, V, dK, dV per head (N counts the queries)
 };
 
 hipError_t attn_fwd_dispatch(const void*, const void*, const void*, void*, float*, int, int, int,
@@ -33,10 +34,11 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-Layout contiguous(int H, int N, int d, int H_kv = 0) {
+Layout contiguous(int H, int N, int d, int H_kv = 0, int Nk = 0) {
   if (H_kv <= 0) H_kv = H;
+  if (Nk <= 0) Nk = N;
   return Layout{(long long)H * N * d, (long long)N * d, d, H,
-                (long long)H_kv * N * d, (long long)N * d, H / H_kv};
+                (long long)H_kv * Nk * d, (long long)Nk * d, H / H_kv, Nk};
 }
 
 // Strides of the strided entry points: positive multiples of 8 elements (rows start on 16-byte
@@ -120,7 +122,7 @@ extern "C" int attn_fwd_strided(const void* Q, const void* K, const void* V, voi
                                 int variant, float beta, float eps, void* stream) {
   if (B < 0 || H < 0 || N < 0 || d < 0) return ATTN_ERR_BAD_ARG;
   if (!strides_ok(stride_b, stride_h, stride_n, d)) return ATTN_ERR_BAD_ARG;
-  const Layout lay{stride_b, stride_h, (int)stride_n, H, stride_b, stride_h, 1};
+  const Layout lay{stride_b, stride_h, (int)stride_n, H, stride_b, stride_h, 1, N};
   return fwd_entry(Q, K, V, O, LSE, nullptr, nullptr, nullptr, B, H, N, d, causal, softmax_scale,
                    variant, beta, eps, 0u, &lay, stream);
 }
@@ -268,7 +270,7 @@ extern "C" int attn_bwd_strided(const void* Q, const void* K, const void* V, con
                                 int variant, void* stream) {
   if (B < 0 || H < 0 || N < 0 || d < 0) return ATTN_ERR_BAD_ARG;
   if (!strides_ok(stride_b, stride_h, stride_n, d)) return ATTN_ERR_BAD_ARG;
-  const Layout lay{stride_b, stride_h, (int)stride_n, H, stride_b, stride_h, 1};
+  const Layout lay{stride_b, stride_h, (int)stride_n, H, stride_b, stride_h, 1, N};
   return bwd_entry(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, H, N, d, causal,
                    softmax_scale, variant, &lay, stream);
 }
@@ -313,5 +315,35 @@ extern "C" int attn_bwd_gqa(const void* Q, const void* K, const void* V, const v
   if (B > 0 && H > 0 && !gqa_heads_ok(H, H_kv)) return ATTN_ERR_BAD_ARG;
   const Layout lay = (B > 0 && H > 0) ? contiguous(H, N, d, H_kv) : contiguous(1, N, d);
   return bwd_entry(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, H, N, d, causal,
+                   softmax_scale, variant, &lay, stream);
+}
+
+// Different numbers of queries and keys.
+static int check_rect(int B, int H, int Nq, int Nk, int d) {
+  if (B < 0 || H < 0 || Nq < 0 || Nk < 0 || d < 0) return ATTN_ERR_BAD_ARG;
+  bool empty;
+  int st = check_shape(B, H, Nk, d, &empty);      // size limits also for the key side
+  if (st != ATTN_OK) return st;
+  return ATTN_OK;
+}
+
+extern "C" int attn_fwd_rect(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                             int B, int H, int Nq, int Nk, int d, int causal, float softmax_scale,
+                             int variant, float beta, float eps, void* stream) {
+  int st = check_rect(B, H, Nq, Nk, d);
+  if (st != ATTN_OK) return st;
+  const Layout lay = (B > 0 && H > 0) ? contiguous(H, Nq, d, 0, Nk) : contiguous(1, 1, d);
+  return fwd_entry(Q, K, V, O, LSE, nullptr, nullptr, nullptr, B, H, Nq, d, causal, softmax_scale,
+                   variant, beta, eps, 0u, &lay, stream);
+}
+
+extern "C" int attn_bwd_rect(const void* Q, const void* K, const void* V, const void* O,
+                             const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
+                             void* workspace, size_t workspace_bytes, int B, int H, int Nq, int Nk,
+                             int d, int causal, float softmax_scale, int variant, void* stream) {
+  int st = check_rect(B, H, Nq, Nk, d);
+  if (st != ATTN_OK) return st;
+  const Layout lay = (B > 0 && H > 0) ? contiguous(H, Nq, d, 0, Nk) : contiguous(1, 1, d);
+  return bwd_entry(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, H, Nq, d, causal,
                    softmax_scale, variant, &lay, stream);
 }

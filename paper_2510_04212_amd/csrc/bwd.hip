@@ -63,7 +63,11 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
   const int wave = tid >> 6;
   const int r = lane & 31, h = lane >> 5;
 
-  const int nkt = (N + kKeysPerWG - 1) / kKeysPerWG;   // N need not be a multiple of the block
+  // RAGGED: the bounds-checking instantiation: N queries and NK keys, neither need be a multiple
+  // of the block; causal mask  key <= query + shift.
+  const int NK = RAGGED ? lay.Nk : N;
+  const int shift = RAGGED ? NK - N : 0;
+  const int nkt = (NK + kKeysPerWG - 1) / kKeysPerWG;
   // Under the causal mask key block kt meets nkt - kt query blocks' worth of tiles: a work-group
   // takes block kt and then its mirror image nkt - 1 - kt, so that all work-groups carry the same
   // load (and there are half as many to start and drain).
@@ -92,7 +96,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
 
     // K_j^T / V_j^T fragments (B operands): lane (r,h) holds K[kw + r][16kc + 8h .. +7]
     // (keys past the sequence end read the last row; their gradients are not stored)
-    const int keyc = (RAGGED && kw + r >= N) ? N - 1 : kw + r;
+    const int keyc = (RAGGED && kw + r >= NK) ? NK - 1 : kw + r;
     bf16x8 kf[D / 16], vf[D / 16];
 #pragma unroll
     for (int kc = 0; kc < D / 16; ++kc) {
@@ -105,8 +109,16 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
 #pragma unroll
       for (int i = 0; i < 16; ++i) { dVt[db][i] = 0.f; dKt[db][i] = 0.f; }
 
-    const int t0 = CAUSAL ? k0 / kQTile : 0;         // first query tile that sees any key of this block
+    // first query tile that sees any key of this block
+    const int t0 = !CAUSAL ? 0 : !RAGGED ? k0 / kQTile : max(0, k0 - shift) / kQTile;
     const int nt = RAGGED ? (N + kQTile - 1) / kQTile : N / kQTile;
+    if (RAGGED && t0 >= nt) {                        // no query sees these keys (more keys than queries reach): zero gradients
+      if (kw + r < NK) {
+        store_acc_T<D>(dV + head_off + (size_t)(kw + r) * sn, dVt, 1.0f, h);
+        store_acc_T<D>(dK + head_off + (size_t)(kw + r) * sn, dKt, alpha, h);
+      }
+      continue;
+    }
 
     // Q_i / dO_i tiles go global -> LDS asynchronously; L_i (pre-multiplied by log2 e) and -delta_i
     // (64 floats each) pass through one register of threads 0..127.  The dP accumulator starts
@@ -125,8 +137,10 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
       loader.template load_rows<RAGGED>(ldsdO + buf * TILE_BYTES, dOp, t * kQTile, N, tid);
       const int row = t * kQTile + (tid & (kQTile - 1));
       const int rowc = (RAGGED && row >= N) ? N - 1 : row;
-      if (tid < kQTile) sreg = Lp[rowc] * kLog2e;
-      else if (tid < 2 * kQTile) sreg = -Dp[rowc];   // LDS holds -delta
+      if (tid < kQTile) {
+        sreg = Lp[rowc] * kLog2e;
+        if (RAGGED && sreg == -INFINITY) sreg = 0.f;   // a query that sees no key: all its scores are masked below
+      } else if (tid < 2 * kQTile) sreg = -Dp[rowc];   // LDS holds -delta
     };
     auto store_stats = [&](int buf) {
       if (tid < kQTile) ldsL[buf * kQTile + tid] = sreg;
@@ -191,7 +205,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
             float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l4[e]));
             if (DIAG) {
               int q = qb0 + 8 * g + 4 * h + e;
-              if (key > q) p = 0.f;
+              if (key > q + shift) p = 0.f;
             }
             float ds = p * dp[i];                     // dp already holds dP - delta
             pf[i >> 3][i & 7] = (bf16_t)p;
@@ -302,15 +316,15 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
           __builtin_amdgcn_sched_barrier(0);
         }
       };
-      if ((!CAUSAL || qt0 >= kw + 31) && (!RAGGED || qt0 + kQTile <= N)) {
+      if ((!CAUSAL || qt0 + shift >= kw + 31) && (!RAGGED || qt0 + kQTile <= N)) {
         tile_pipelined();
       } else {
 #pragma unroll
         for (int qb = 0; qb < kQTile / 32; ++qb) {
           const int qb0 = qt0 + 32 * qb;
-          if (CAUSAL && qb0 + 31 < kw) continue;     // every query of the block precedes every key of the wave
+          if (CAUSAL && qb0 + shift + 31 < kw) continue;   // no query of the block sees a key of the wave
           if (RAGGED && qb0 >= N) continue;                    // nothing but padding
-          if (CAUSAL && qb0 < kw + 31) qblock(std::true_type{}, qb);
+          if (CAUSAL && qb0 + shift < kw + 31) qblock(std::true_type{}, qb);
           else qblock(std::false_type{}, qb);
         }
       }
@@ -334,7 +348,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
         }
       }
     }
-    if (!RAGGED || kw + r < N) {
+    if (!RAGGED || kw + r < NK) {
       store_acc_T<D>(dV + head_off + (size_t)(kw + r) * sn, dVt, 1.0f, h);
       store_acc_T<D>(dK + head_off + (size_t)(kw + r) * sn, dKt, alpha, h);
     }
@@ -359,6 +373,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
   const int wave = tid >> 6;
   const int r = lane & 31, h = lane >> 5;
 
+  const int NK = RAGGED ? lay.Nk : N;                 // bounds-checking instantiation: N queries, NK keys,
+  const int shift = RAGGED ? NK - N : 0;              // causal mask  key <= query + shift
   const int nqt = (N + kQPerWG - 1) / kQPerWG;
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nqt;
@@ -379,7 +395,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     qf[kc] = *reinterpret_cast<const bf16x8*>(Q + head_off + (size_t)qc * sn + 16 * kc + 8 * h);
     dof[kc] = *reinterpret_cast<const bf16x8*>(dO + head_off + (size_t)qc * sn + 16 * kc + 8 * h);
   }
-  const float l2 = LSE[(size_t)bh * N + qc] * kLog2e;
+  float l2 = LSE[(size_t)bh * N + qc] * kLog2e;
+  if (RAGGED && l2 == -INFINITY) l2 = 0.f;             // a query that sees no key: all its scores are masked below
   const float dl = DELTA_MODE ? 0.f : delta[(size_t)bh * N + qc];
   float pdp = 0.f;                                   // DELTA_MODE: this lane's share of sum_k P dP
   // -delta_i in all 16 accumulator slots of the lane: the third operand of the first dP^T matrix
@@ -395,14 +412,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) dQt[db][i] = 0.f;
 
-  const int kend = CAUSAL ? ((RAGGED && q0 + kQPerWG > N) ? N : q0 + kQPerWG) : N;
+  const int kend = !CAUSAL ? NK : !RAGGED ? q0 + kQPerWG : max(0, min(NK, q0 + kQPerWG + shift));
   const int ntiles = RAGGED ? (kend + kKTile - 1) / kKTile : kend / kKTile;
   const float c2 = alpha * kLog2e;
 
   TileLoader<D> loader;
   loader.init(tid, sn);
-  loader.template load_rows<RAGGED>(ldsK, Kh, 0, N, tid);
-  loader.template load_rows<RAGGED>(ldsV, Vh, 0, N, tid);
+  loader.template load_rows<RAGGED>(ldsK, Kh, 0, NK, tid);
+  loader.template load_rows<RAGGED>(ldsV, Vh, 0, NK, tid);
   wait_vmem();
   __syncthreads();
 
@@ -412,15 +429,15 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const char* tV = smem + (2 + buf) * TILE_BYTES;
     const bool has_next = (j + 1 < ntiles);
     if (has_next) {
-      loader.template load_rows<RAGGED>(smem + (buf ^ 1) * TILE_BYTES, Kh, (j + 1) * kKTile, N, tid);
-      loader.template load_rows<RAGGED>(smem + (2 + (buf ^ 1)) * TILE_BYTES, Vh, (j + 1) * kKTile, N, tid);
+      loader.template load_rows<RAGGED>(smem + (buf ^ 1) * TILE_BYTES, Kh, (j + 1) * kKTile, NK, tid);
+      loader.template load_rows<RAGGED>(smem + (2 + (buf ^ 1)) * TILE_BYTES, Vh, (j + 1) * kKTile, NK, tid);
     }
     const int kt0 = j * kKTile;
-    if (!CAUSAL || (kt0 <= qw + 31)) {
+    if (!CAUSAL || (kt0 <= qw + shift + 31)) {
       auto kblock = [&](auto diag_c, int kb) {
         constexpr bool DIAG = decltype(diag_c)::value;
         const int kb0 = kt0 + 32 * kb;
-        const bool tail = RAGGED && kb0 + 32 > N;            // some keys lie past the sequence end
+        const bool tail = RAGGED && kb0 + 32 > NK;           // some keys lie past the sequence end
         // ---- S^T = K_j Q_i^T, dP^T = V_j dO_i^T ; rows = keys, lane = query
         f32x16 s, dp;
 #pragma unroll
@@ -434,7 +451,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
         if (tail) {   // keys past the sequence end: P = exp(-inf) = 0, so they add nothing to dQ
 #pragma unroll
           for (int i = 0; i < 16; ++i)
-            if (kb0 + 8 * (i >> 2) + 4 * h + (i & 3) >= N) s[i] = -INFINITY;
+            if (kb0 + 8 * (i >> 2) + 4 * h + (i & 3) >= NK) s[i] = -INFINITY;
         }
         bf16x8 dsf[2];
         const int q = qw + r;
@@ -443,7 +460,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
           float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l2));
           if (DIAG) {
             int key = kb0 + 8 * (i >> 2) + 4 * h + (i & 3);
-            if (key > q) p = 0.f;
+            if (key > q + shift) p = 0.f;
           }
           if (DELTA_MODE) pdp = __builtin_fmaf(p, dp[i], pdp);
           else dsf[i >> 3][i & 7] = (bf16_t)(p * dp[i]);      // dp already holds dP - delta
@@ -462,9 +479,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
 #pragma unroll
       for (int kb = 0; kb < kKTile / 32; ++kb) {
         const int kb0 = kt0 + 32 * kb;
-        if (CAUSAL && (kb0 > qw + 31)) continue;   // every key of the block follows every query of the wave
-        if (RAGGED && kb0 >= N) continue;                    // nothing but padding
-        if (CAUSAL && (kb0 + 31 > qw)) kblock(std::true_type{}, kb);
+        if (CAUSAL && (kb0 > qw + shift + 31)) continue;   // no query of the wave sees a key of the block
+        if (RAGGED && kb0 >= NK) continue;                   // nothing but padding
+        if (CAUSAL && (kb0 + 31 > qw + shift)) kblock(std::true_type{}, kb);
         else kblock(std::false_type{}, kb);
       }
     }
@@ -497,7 +514,7 @@ static hipError_t launch_dkdv(const void* Q, const void* K, const void* V, const
   auto k = attn_bwd_dkdv_kernel<D, CAUSAL, RAGGED, GROUPED>;
   hipError_t e;
   if ((e = set_smem(k, smem, set)) != hipSuccess) return e;
-  const int nkt = (N + kKeysPerWG - 1) / kKeysPerWG;
+  const int nkt = ((RAGGED ? lay.Nk : N) + kKeysPerWG - 1) / kKeysPerWG;
   hipLaunchKernelGGL(k, dim3((BH / lay.group) * (CAUSAL ? (nkt + 1) / 2 : nkt)), dim3(256), smem, st, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
                      (bf16_t*)dK, (bf16_t*)dV, N, alpha, lay);
@@ -525,7 +542,7 @@ hipError_t attn_bwd_dkdv_dispatch(const void* Q, const void* K, const void* V, c
                                   const float* LSE, const float* delta, void* dK, void* dV,
                                   int BH, int N, int d, int causal, float alpha, Layout lay,
                                   hipStream_t st) {
-  const bool ragged = (N % kKeysPerWG) != 0;     // the aligned kernels carry no bounds handling
+  const bool ragged = (N % kKeysPerWG) != 0 || lay.Nk != N;   // the aligned kernels carry no bounds handling
   if (lay.group > 1) {   // grouped queries: the bounds-checking instantiation serves every N
 #define CASEG(DD, CC)                                 \
   if (d == DD && (causal != 0) == CC)                 \
@@ -546,7 +563,7 @@ hipError_t attn_bwd_dkdv_dispatch(const void* Q, const void* K, const void* V, c
 hipError_t attn_bwd_dq_dispatch(const void* Q, const void* K, const void* V, const void* dO,
                                 const float* LSE, const float* delta, void* dQ, int BH, int N,
                                 int d, int causal, float alpha, Layout lay, hipStream_t st) {
-  const bool ragged = (N % kQPerWG) != 0;
+  const bool ragged = (N % kQPerWG) != 0 || lay.Nk != N;
 #define CASE(DD, CC, RR)                                                \
   if (d == DD && (causal != 0) == CC && ragged == RR)                   \
     return launch_dq<DD, CC, RR, false>(Q, K, V, dO, LSE, delta, dQ, nullptr, BH, N, alpha, lay, st);

@@ -132,12 +132,17 @@ DEVI float sum_with_partner32(float x) {
 // optional float32 / int32 outputs are always contiguous [B,H,N(,d)].
 // Grouped-query attention: K, V, dK, dV have H / group heads with their own batch / head strides
 // (sb_kv, sh_kv); query head h uses key/value head h / group.  group = 1 is ordinary attention.
+// Nk: rows of K, V, dK, dV per head.  The kernels' sequence-length argument N counts the queries
+// (rows of Q, O, dO, dQ, LSE, delta).  Only the bounds-checking kernel instantiations read Nk
+// (the others are used for N == Nk, multiples of the block size); with Nk != N the causal mask
+// is aligned at the bottom right: query r sees keys c <= r + (Nk - N).
 struct Layout {
   long long sb, sh;
   int sn;
   int H;
   long long sb_kv, sh_kv;
   int group;
+  int Nk;
 };
 // first element of query-side head bh = b*H + h
 DEVI size_t head_base(const Layout& lay, int bh) {

@@ -51,8 +51,11 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
   const int wave = tid >> 6;
   const int r = lane & 31, h = lane >> 5;
 
-  // RAGGED: N is not a multiple of the block; the last block's missing rows are computed on
-  // clamped data and not stored, and keys past the end are masked like future keys.
+  // RAGGED: the bounds-checking instantiation.  N (queries) need not be a multiple of the block:
+  // the last block's missing rows are computed on clamped data and not stored; NK keys, those
+  // past the end are masked like future keys; the causal mask is  key <= query + shift.
+  const int NK = RAGGED ? lay.Nk : N;
+  const int shift = RAGGED ? NK - N : 0;
   const int nqt = (N + kBr - 1) / kBr;
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nqt;
@@ -73,10 +76,11 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
   FragOffsets<D> fo;
   init_frag_offsets<D>(fo, lane);
 
-  const int kend = CAUSAL ? ((RAGGED && q0 + kBr > N) ? N : q0 + kBr) : N;   // keys [0, kend) can matter to this block
+  // keys [0, kend) can matter to this block
+  const int kend = !CAUSAL ? NK : !RAGGED ? q0 + kBr : max(0, min(NK, q0 + kBr + shift));
   const int ntiles = RAGGED ? (kend + kBc - 1) / kBc : kend / kBc;
-  loader.template load_rows<RAGGED>(smem, Kh, 0, N, tid);
-  if (VARIANT != kRowStats) loader.template load_rows<RAGGED>(smem + 2 * TILE_BYTES, Vh, 0, N, tid);
+  loader.template load_rows<RAGGED>(smem, Kh, 0, NK, tid);
+  if (VARIANT != kRowStats) loader.template load_rows<RAGGED>(smem + 2 * TILE_BYTES, Vh, 0, NK, tid);
 
   // Q_i^T fragments: lane (r,h) holds Q[qw + r][16kc + 8h .. +7] for every kc.
   bf16x8 qf[D / 16];
@@ -110,13 +114,13 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
     const char* tK = smem + BUF * TILE_BYTES;
     const char* tV = smem + (2 + BUF) * TILE_BYTES;
     if (j + 1 < ntiles) {   // lands in the other buffer while this tile is being processed
-      loader.template load_rows<RAGGED>(smem + (BUF ^ 1) * TILE_BYTES, Kh, (j + 1) * kBc, N, tid);
+      loader.template load_rows<RAGGED>(smem + (BUF ^ 1) * TILE_BYTES, Kh, (j + 1) * kBc, NK, tid);
       if (VARIANT != kRowStats)
-        loader.template load_rows<RAGGED>(smem + (2 + (BUF ^ 1)) * TILE_BYTES, Vh, (j + 1) * kBc, N, tid);
+        loader.template load_rows<RAGGED>(smem + (2 + (BUF ^ 1)) * TILE_BYTES, Vh, (j + 1) * kBc, NK, tid);
     }
     const int k0 = j * kBc;
     // A wave whose 32 rows all lie above this key tile has nothing to do in it (causal).
-    if (!CAUSAL || (k0 <= qw + 31)) {
+    if (!CAUSAL || (k0 <= qw + shift + 31)) {
       // ---- S^T = K_j Q_i^T (Alg. 1 step 6); raw scores, alpha not yet applied
       f32x16 s[2];
 #pragma unroll
@@ -131,13 +135,13 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
       sched_reads_ahead_of_mfma<D / 8, 1, 4>();
       // ---- mask: causal (key > query) in the tile that crosses the diagonal, and keys beyond
       // the sequence end in the last, partial tile -> -inf
-      if ((CAUSAL && (k0 + kBc - 1 > qw)) || (RAGGED && k0 + kBc > N)) {
+      if ((CAUSAL && (k0 + kBc - 1 > qw + shift)) || (RAGGED && k0 + kBc > NK)) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             int key = k0 + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
-            if ((CAUSAL && key > q) || (RAGGED && key >= N)) s[kb][i] = -INFINITY;
+            if ((CAUSAL && key > q + shift) || (RAGGED && key >= NK)) s[kb][i] = -INFINITY;
           }
       }
       if (VARIANT == kRowStats) {
@@ -153,7 +157,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
         float corr = 1.f;    // factor the accumulated output and row sum are multiplied by
         float mneg;          // -m log2(e) of the normaliser used for this tile
         if (VARIANT == kFixedNorm) {
-          mneg = -m * kLog2e;
+          mneg = (RAGGED && m == -INFINITY) ? 0.f : -m * kLog2e;   // a query that sees no key at all
         } else {
           // ---- tile row maximum r_m (of the alpha-scaled scores)
           float mx = s[0][0];
@@ -184,15 +188,17 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
             const unsigned long long once_sw = (once >> 32) | (once << 32);
             const unsigned long long twice_sw = (twice >> 32) | (twice << 32);
             const unsigned long long rep = twice | twice_sw | (once & once_sw);
-            const bool repeated = ((rep >> lane) & 1ull) != 0ull;
+            // (a row with nothing visible in this tile has r_m = -inf: no rule, no update)
+            const bool repeated = ((rep >> lane) & 1ull) != 0ull && (!RAGGED || mx > -INFINITY);
             m_prime = (repeated && r_m > 0.f) ? beta * r_m : r_m;
             m_prime = (repeated && r_m < 0.f) ? 0.f : m_prime;
             if (EXTRAS) fired_cnt += (m_prime != r_m) ? 1 : 0;
           }
           const float m_new = fmaxf(m, m_prime);         // Alg. 1 step 7 / Alg. 3
-          corr = __builtin_amdgcn_exp2f((m - m_new) * kLog2e);
+          const bool unseen = RAGGED && m_new == -INFINITY;   // nothing visible so far: P-bar = 0, nothing to rescale
+          corr = unseen ? 1.f : __builtin_amdgcn_exp2f((m - m_new) * kLog2e);
           m = m_new;
-          mneg = -m_new * kLog2e;
+          mneg = unseen ? 0.f : -m_new * kLog2e;
         }
         // ---- P-bar = exp(S - m), rounded to bf16; row sum of the ROUNDED values
         bf16x8 pf[2][2];
@@ -264,6 +270,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
   if (RAGGED && q >= N) return;                            // rows past the sequence end exist only as padding
   bf16_t* Oq = O + head_off + (size_t)q * sn;
   const bool keep_obar_f32 = EXTRAS && ex.single_rounding != 0;
+  const bool unseen_row = RAGGED && m == -INFINITY;        // no visible key (more queries than keys): O = 0, LSE = -inf
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -273,13 +280,13 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
       for (int e = 0; e < 4; ++e) {
         const float a = acc[db][4 * g + e];
         const float obar = keep_obar_f32 ? a : (float)(bf16_t)a;
-        o4[e] = (bf16_t)(obar / l);
+        o4[e] = (bf16_t)(unseen_row ? 0.f : obar / l);
       }
       *reinterpret_cast<bf16x4*>(Oq + 32 * db + 8 * g + 4 * h) = o4;
       if (EXTRAS && ex.O_hp != nullptr) {
         f32x4 hp;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) hp[e] = acc[db][4 * g + e] / l;
+        for (int e = 0; e < 4; ++e) hp[e] = unseen_row ? 0.f : acc[db][4 * g + e] / l;
         *reinterpret_cast<f32x4*>(ex.O_hp + ((size_t)bh * N + q) * D + 32 * db + 8 * g + 4 * h) = hp;
       }
     }
@@ -336,7 +343,7 @@ hipError_t attn_fwd_dispatch(const void* Q, const void* K, const void* V, void* 
 #define CASE(DD, CC, VV)                                                                      \
   if (d == DD && (causal != 0) == CC && variant == VV) {                                       \
     if (extras) return launch_fwd<DD, CC, VV, true, true>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, lay, st); \
-    return (N % kBr) ? launch_fwd<DD, CC, VV, true, false>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, lay, st) \
+    return (N % kBr || lay.Nk != N) ? launch_fwd<DD, CC, VV, true, false>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, lay, st) \
                      : launch_fwd<DD, CC, VV, false, false>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, lay, st); \
   }
   CASE(64, false, 0) CASE(64, false, 1) CASE(64, true, 0) CASE(64, true, 1)

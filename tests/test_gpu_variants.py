@@ -339,6 +339,17 @@ def test_autograd_wrapper(lib):
     dQ, dK, dV = lib.attn_bwd_gqa(q.detach(), k1.detach(), v1.detach(), O, w, L, True, 1.0 / np.sqrt(d), lib.STANDARD)
     torch.cuda.synchronize()
     assert torch.equal(o, O) and torch.equal(q.grad, dQ) and torch.equal(k1.grad, dK) and torch.equal(v1.grad, dV)
+    # fewer queries than keys (a chunk of queries at the end of the sequence)
+    qr = base["q"].permute(0, 2, 1, 3)[:, :, N - 100:].contiguous().requires_grad_(True)
+    kr = base["k"].permute(0, 2, 1, 3).contiguous().requires_grad_(True)
+    vr = base["v"].permute(0, 2, 1, 3).contiguous().requires_grad_(True)
+    wr = base["w"].permute(0, 2, 1, 3)[:, :, N - 100:].contiguous()
+    o = attention(qr, kr, vr, causal=True, variant=lib.MITIGATED)
+    (o.float() * wr.float()).sum().backward()
+    O, L = lib.attn_fwd_rect(qr.detach(), kr.detach(), vr.detach(), True, 1.0 / np.sqrt(d), lib.MITIGATED)
+    dQ, dK, dV = lib.attn_bwd_rect(qr.detach(), kr.detach(), vr.detach(), O, wr, L, True, 1.0 / np.sqrt(d), lib.MITIGATED)
+    torch.cuda.synchronize()
+    assert torch.equal(o, O) and torch.equal(qr.grad, dQ) and torch.equal(kr.grad, dK) and torch.equal(vr.grad, dV)
     q = base["q"].permute(0, 2, 1, 3).contiguous().float().requires_grad_(True)
     opt = torch.optim.SGD([q], lr=1e-2)
     first = None

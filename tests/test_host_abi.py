@@ -86,6 +86,12 @@ def test_argument_validation_happens_on_the_host(binding):
     gq = lambda H, Hkv: lib.attn_fwd_gqa(p, p, p, q, p, 1, H, Hkv, 128, 64, 1, 0.125, 0, 2.0, 1e-3, None)
     assert gq(6, 4) == BAD and gq(4, 0) == BAD and gq(2, 4) == BAD and gq(0, 0) == OK
     assert lib.attn_bwd_gqa(*ptrs_for_strided, ws_for_strided, 4096, 1, 6, 4, 128, 64, 1, 0.125, 0, None) == BAD
+    fr = lambda Nq, Nk, d=64, Q=p: lib.attn_fwd_rect(Q, p, p, q, p, 1, 1, Nq, Nk, d, 1, 0.125, 0, 2.0, 1e-3, None)
+    assert fr(128, 0) == UNSUP and fr(0, 128) == UNSUP and fr(-1, 128) == BAD and fr(128, -1) == BAD
+    assert fr(128, 256, d=96) == UNSUP and fr(128, 256, Q=None) == NULL
+    assert lib.attn_fwd_rect(None, None, None, None, None, 0, 4, 128, 256, 64, 1, 0.125, 0, 2.0, 1e-3, None) == OK
+    br = lambda Nq, Nk, wb: lib.attn_bwd_rect(*ptrs_for_strided, ws_for_strided, wb, 1, 1, Nq, Nk, 64, 1, 0.125, 0, None)
+    assert br(128, 0, 4096) == UNSUP and br(200, 64, 512) == WS     # delta has Nq = 200 floats: 1024 bytes
     rc = lambda *a: lib.attn_delta_recompute(*a, 1, 1, 128, 64, 1, 0.125, None)
     assert rc(p, p, p, p, p, None) == NULL and rc(p, p, p, p, p, p) == BAD and rc(p, p, p, mis, p, q) == BAD
     assert lib.attn_delta_recompute(p, p, p, p, p, q, 1, 1, 128, 64, 1, -1.0, None) == BAD
