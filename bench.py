@@ -157,6 +157,35 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom))},
     }
 
+    # delta pass with cold caches: a 1 GiB fill in front of every timed launch evicts O and dO
+    # from L2 and the 256 MB Infinity Cache (the figure above is a warm one: the forward has just
+    # written O)
+    if not args.only_headline:
+        flush = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        cold = []
+        for _ in range(5):
+            flush.fill_(1)
+            e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            binding.attn_delta(job.O, x["dO"], job.delta, stream=stream)
+            e1.record(stream)
+            e1.synchronize()
+            cold.append(e0.elapsed_time(e1))
+        del flush
+        torch.cuda.empty_cache()
+        cold_ms = float(np.median(cold))
+        out["delta_pass"]["cold_ms"] = round(cold_ms, 4)
+        out["delta_pass"]["cold_GB/s"] = round(delta_bytes / (cold_ms * 1e-3) / 1e9, 1)
+
+    # what the matrix cores sustain on this chip: a loop of matrix instructions on register
+    # operands (attn_probe_matrix_clock), ~3 ms on every SIMD
+    probe = binding.probe_matrix_clock(workgroups=512, iters=25000)
+    out["matrix_core_probe"] = {"shader_clock_ghz": round(probe["shader_clock_ghz"], 3),
+                                "measured_mfma_tflops": round(probe["tflops"], 1),
+                                "frac_of_measured_mfma_rate": round(tflops / probe["tflops"], 4),
+                                "note": "pure v_mfma_f32_32x32x16_bf16 loop, no memory traffic; nominal peak "
+                                        f"{PEAK_BF16_TFLOPS:.0f} TFLOP/s assumes 2.4 GHz"}
+
     # the other two throughput workloads of the build target, same step, fewer repetitions
     also = {}
     for name in ("gpt2s", "mid", "long"):

@@ -241,6 +241,18 @@ int attn_bwd_rect(const void* Q, const void* K, const void* V, const void* O, co
                   int B, int H, int Nq, int Nk, int d, int causal, float softmax_scale, int variant,
                   void* stream);
 
+/*
+ * Measurement aid for benchmarks (no attention arithmetic, nothing from the paper): runs
+ * `workgroups` work-groups of 4 waves, each wave issuing 4 * iters independent
+ * v_mfma_f32_32x32x16_bf16 instructions on register operands, and writes to the DEVICE array
+ * out[0..2] (16-byte aligned, 3 x int64): out[0] = shader-clock cycles and out[1] = ticks of the
+ * constant 100 MHz counter that the first wave spent in its loop (out[2] is scratch).
+ * out[0] / (out[1] / 1e8) is the shader clock sustained under matrix load; the caller times the
+ * launch to get the instruction rate.  1 <= workgroups <= 65536, 1 <= iters <= 2^22
+ * (ATTN_ERR_BAD_ARG otherwise).  Enqueued on `stream` like everything else.
+ */
+int attn_probe_matrix_clock(long long* out, int workgroups, int iters, void* stream);
+
 /* Human-readable name of an attn_status (static storage, never NULL). */
 const char* attn_status_string(int status);
 

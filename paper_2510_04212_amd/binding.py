@@ -51,6 +51,8 @@ _lib.attn_fwd_rect.argtypes = [_vp] * 5 + [_i, _i, _i, _i, _i, _i, _f, _i, _f, _
 _lib.attn_fwd_rect.restype = _i
 _lib.attn_bwd_rect.argtypes = [_vp] * 9 + [_vp, _sz, _i, _i, _i, _i, _i, _i, _f, _i, _vp]
 _lib.attn_bwd_rect.restype = _i
+_lib.attn_probe_matrix_clock.argtypes = [_vp, _i, _i, _vp]
+_lib.attn_probe_matrix_clock.restype = _i
 _lib.attn_bwd.argtypes = [_vp] * 9 + [_vp, _sz, _i, _i, _i, _i, _i, _f, _i, _vp]
 _lib.attn_bwd.restype = _i
 _lib.attn_bwd_dkdv.argtypes = [_vp] * 8 + [_i, _i, _i, _i, _i, _f, _vp]
@@ -71,7 +73,7 @@ EXPORTS = ["attn_fwd", "attn_fwd_ex", "attn_fwd_opt", "attn_delta", "attn_delta_
            "attn_bwd_dkdv", "attn_bwd_dq", "attn_fwd_strided", "attn_bwd_strided",
            "attn_fwd_gqa", "attn_bwd_gqa", "attn_fwd_rect", "attn_bwd_rect",
            "attn_bwd_workspace_bytes",
-           "attn_status_string", "attn_fwd_key_tile"]
+           "attn_status_string", "attn_fwd_key_tile", "attn_probe_matrix_clock"]
 
 
 class AttnError(RuntimeError):
@@ -362,3 +364,21 @@ def attn_bwd_rect(Q, K, V, O, dO, LSE, causal, softmax_scale, variant=STANDARD, 
                               _ptr(dV), _ptr(workspace), workspace.numel(), B, H, Nq, Nk, d,
                               int(bool(causal)), float(softmax_scale), int(variant), _stream(stream)))
     return dQ, dK, dV
+
+
+def probe_matrix_clock(workgroups=512, iters=50000, stream=None):
+    """Runs the library's matrix-instruction loop (attn_probe_matrix_clock) and returns a dict:
+    shader clock in GHz sustained under matrix load, elapsed milliseconds of the launch, and the
+    matrix-instruction rate in TFLOP/s (4 waves x 4 iters instructions of 32768 FLOP per work-group)."""
+    out = torch.zeros(4, dtype=torch.int64, device="cuda")
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    s = torch.cuda.current_stream() if stream is None else stream
+    e0.record(s)
+    _check(_lib.attn_probe_matrix_clock(_ptr(out), int(workgroups), int(iters), _stream(stream)))
+    e1.record(s)
+    e1.synchronize()
+    ms = e0.elapsed_time(e1)
+    cyc, ticks = out[0].item(), out[1].item()
+    flop = float(workgroups) * 4 * 4 * iters * 32768.0
+    return {"shader_clock_ghz": cyc / (ticks / 1e8) / 1e9 if ticks else float("nan"),
+            "ms": ms, "tflops": flop / (ms * 1e-3) / 1e12}

@@ -400,3 +400,16 @@ def test_grouped_query_attention(lib, H, Hkv, N, d, causal):
                 assert metrics.rel_l2(got, ref) <= TOL_REL
                 # a sum of `group` heads: magnitudes and bf16 steps grow with the group
                 assert metrics.max_abs(got, ref) <= max(TOL_ABS, 2.0 ** -8 * np.abs(ref).max())
+
+
+def test_matrix_clock_probe(lib):
+    """The benchmark's measurement aid: plausible clock and rate, argument checks."""
+    p = lib.probe_matrix_clock(workgroups=512, iters=2000)
+    print(f"\nprobe: {p['shader_clock_ghz']:.2f} GHz, {p['tflops']:.0f} TFLOP/s over {p['ms']:.2f} ms")
+    assert 0.8 < p["shader_clock_ghz"] < 2.7
+    assert 300 < p["tflops"] < 2600
+    out = torch.zeros(4, dtype=torch.int64, device=DEV)
+    raw = lib.raw()
+    assert raw.attn_probe_matrix_clock(out.data_ptr(), 0, 10, None) == 2
+    assert raw.attn_probe_matrix_clock(out.data_ptr(), 8, 0, None) == 2
+    assert raw.attn_probe_matrix_clock(None, 8, 10, None) == 1
