@@ -163,15 +163,19 @@ int attn_bwd(const void* Q, const void* K, const void* V, const void* O, const v
 size_t attn_bwd_workspace_bytes(int B, int H, int N, int d);
 
 /*
- * The two main stages of attn_bwd, exposed separately so that a caller can time them
- * (attn_bwd == attn_delta into the workspace, then attn_bwd_dkdv, then attn_bwd_dq).
- * `delta` is float32 [B,H,N] as produced by attn_delta.  Same layouts, checks and error codes
- * as attn_bwd.
- *   attn_bwd_dkdv  Alg. 2 steps 8-12 and 10/14 for one key block per work-group:
- *                  S = Q K^T, P = exp(S - L), dP = dO V^T, dS = P o (dP - delta),
- *                  dV = P^T dO, dK = alpha dS^T Q.
- *   attn_bwd_dq    Alg. 2 steps 8-13 for one query block per work-group (S and dP recomputed):
- *                  dQ = alpha dS K.
+ * The stages of attn_bwd, exposed separately so that a caller can time them or feed them
+ * another delta.  attn_bwd == attn_bwd_dq_delta (delta into the workspace), then attn_bwd_dkdv;
+ * attn_delta, then attn_bwd_dkdv and attn_bwd_dq in either order, gives the same bits.
+ * `delta` is float32 [B,H,N].  Same layouts, checks and error codes as attn_bwd.
+ *   attn_bwd_dkdv      Alg. 2 steps 8-12 and 10/14 for one key block per work-group:
+ *                      S = Q K^T, P = exp(S - L), dP = dO V^T, dS = P o (dP - delta),
+ *                      dV = P^T dO, dK = alpha dS^T Q.  `delta` is an input.
+ *   attn_bwd_dq        Alg. 2 steps 8-13 for one query block per work-group (S and dP recomputed):
+ *                      dQ = alpha dS K.  `delta` is an input.
+ *   attn_bwd_dq_delta  the same, and Alg. 2 step 4 on the way: each work-group first forms
+ *                      delta = rowsum(dO o O) for its own query rows (it holds their dO already),
+ *                      writes it to `delta` (an OUTPUT here) and uses it.  The sum is taken in
+ *                      attn_delta's order: identical bits, one pass over O and dO saved.
  */
 int attn_bwd_dkdv(const void* Q, const void* K, const void* V, const void* dO, const float* LSE,
                   const float* delta, void* dK, void* dV,
@@ -179,6 +183,9 @@ int attn_bwd_dkdv(const void* Q, const void* K, const void* V, const void* dO, c
 int attn_bwd_dq(const void* Q, const void* K, const void* V, const void* dO, const float* LSE,
                 const float* delta, void* dQ,
                 int B, int H, int N, int d, int causal, float softmax_scale, void* stream);
+int attn_bwd_dq_delta(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                      const float* LSE, void* dQ, float* delta,
+                      int B, int H, int N, int d, int causal, float softmax_scale, void* stream);
 
 /*
  * Strided forms of attn_fwd_ex and attn_bwd: element (b, h, n, k) of every bf16 tensor of the

@@ -58,6 +58,8 @@ _lib.attn_bwd.restype = _i
 _lib.attn_bwd_dkdv.argtypes = [_vp] * 8 + [_i, _i, _i, _i, _i, _f, _vp]
 _lib.attn_bwd_dkdv.restype = _i
 _lib.attn_bwd_dq.argtypes = [_vp] * 7 + [_i, _i, _i, _i, _i, _f, _vp]
+_lib.attn_bwd_dq_delta.argtypes = [_vp] * 8 + [_i, _i, _i, _i, _i, _f, _vp]
+_lib.attn_bwd_dq_delta.restype = _i
 _lib.attn_bwd_dq.restype = _i
 _lib.attn_bwd_workspace_bytes.argtypes = [_i, _i, _i, _i]
 _lib.attn_bwd_workspace_bytes.restype = _sz
@@ -70,7 +72,7 @@ FWD_SINGLE_ROUNDING = 1
 
 EXPORTS = ["attn_fwd", "attn_fwd_ex", "attn_fwd_opt", "attn_delta", "attn_delta_hp",
            "attn_delta_recompute", "attn_bwd",
-           "attn_bwd_dkdv", "attn_bwd_dq", "attn_fwd_strided", "attn_bwd_strided",
+           "attn_bwd_dkdv", "attn_bwd_dq", "attn_bwd_dq_delta", "attn_fwd_strided", "attn_bwd_strided",
            "attn_fwd_gqa", "attn_bwd_gqa", "attn_fwd_rect", "attn_bwd_rect",
            "attn_bwd_workspace_bytes",
            "attn_status_string", "attn_fwd_key_tile", "attn_probe_matrix_clock"]
@@ -245,6 +247,18 @@ def attn_bwd_dq(Q, K, V, dO, LSE, delta, causal, softmax_scale, dQ=None, stream=
     _check(_lib.attn_bwd_dq(_ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(LSE), _ptr(delta), _ptr(dQ),
                             B, H, N, d, int(bool(causal)), float(softmax_scale), _stream(stream)))
     return dQ
+
+
+def attn_bwd_dq_delta(Q, K, V, O, dO, LSE, causal, softmax_scale, dQ=None, delta=None, stream=None):
+    """First stage of attn_bwd: dQ, and delta = rowsum(dO o O) formed on the way (returned too)."""
+    B, H, N, d = _bhnd(Q, "Q")
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    if delta is None:
+        delta = torch.empty((B, H, N), dtype=torch.float32, device=Q.device)
+    _check(_lib.attn_bwd_dq_delta(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ),
+                                  _ptr(delta), B, H, N, d, int(bool(causal)), float(softmax_scale),
+                                  _stream(stream)))
+    return dQ, delta
 
 
 def _strided_bhnd(t, name, like=None):

@@ -24,8 +24,8 @@ hipError_t attn_bwd_dkdv_dispatch(const void*, const void*, const void*, const v
                                   const float*, void*, void*, int, int, int, int, float, Layout,
                                   hipStream_t);
 hipError_t attn_bwd_dq_dispatch(const void*, const void*, const void*, const void*, const float*,
-                                const float*, void*, int, int, int, int, float, Layout,
-                                hipStream_t);
+                                const float*, const void*, void*, float*, int, int, int, int,
+                                float, Layout, hipStream_t);
 hipError_t attn_delta_recompute_dispatch(const void*, const void*, const void*, const void*,
                                          const float*, float*, int, int, int, int, float, Layout,
                                          hipStream_t);
@@ -217,7 +217,29 @@ extern "C" int attn_bwd_dq(const void* Q, const void* K, const void* V, const vo
   const void* ins[] = {Q, K, V, dO};
   for (const void* p : ins)
     if (p == dQ) return ATTN_ERR_BAD_ARG;
-  hipError_t e = attn_bwd_dq_dispatch(Q, K, V, dO, LSE, delta, dQ, B * H, N, d, causal,
+  hipError_t e = attn_bwd_dq_dispatch(Q, K, V, dO, LSE, delta, nullptr, dQ, nullptr, B * H, N, d,
+                                      causal, softmax_scale, contiguous(H, N, d),
+                                      static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+extern "C" int attn_bwd_dq_delta(const void* Q, const void* K, const void* V, const void* O,
+                                 const void* dO, const float* LSE, void* dQ, float* delta, int B,
+                                 int H, int N, int d, int causal, float softmax_scale,
+                                 void* stream) {
+  bool empty;
+  int st = check_bwd_common(B, H, N, d, softmax_scale, &empty);
+  if (st != ATTN_OK) return st;
+  if (empty) return ATTN_OK;
+  if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !delta) return ATTN_ERR_NULL;
+  const void* ptrs[] = {Q, K, V, O, dO, LSE, dQ, delta};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return ATTN_ERR_BAD_ARG;
+  const void* ins[] = {Q, K, V, O, dO, LSE};
+  for (const void* p : ins)
+    if (p == dQ || p == static_cast<const void*>(delta)) return ATTN_ERR_BAD_ARG;
+  if (dQ == static_cast<void*>(delta)) return ATTN_ERR_BAD_ARG;
+  hipError_t e = attn_bwd_dq_dispatch(Q, K, V, dO, LSE, nullptr, O, dQ, delta, B * H, N, d, causal,
                                       softmax_scale, contiguous(H, N, d),
                                       static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
@@ -248,11 +270,12 @@ static int bwd_entry(const void* Q, const void* K, const void* V, const void* O,
   hipStream_t s = static_cast<hipStream_t>(stream);
   float* delta = static_cast<float*>(workspace);
   const Layout lay = user_lay ? *user_lay : contiguous(H, N, d);
-  hipError_t e = attn_delta_dispatch(O, dO, delta, (long)B * H * N, N, d, 0, lay, s);
+  // the dQ kernel forms delta = rowsum(dO o O) for its own rows (Alg. 2 step 4) and leaves it in
+  // the workspace for the dK/dV kernel: no separate pass over O and dO
+  hipError_t e = attn_bwd_dq_dispatch(Q, K, V, dO, LSE, nullptr, O, dQ, delta, B * H, N, d, causal,
+                                      softmax_scale, lay, s);
   if (e != hipSuccess) return ATTN_ERR_LAUNCH;
   e = attn_bwd_dkdv_dispatch(Q, K, V, dO, LSE, delta, dK, dV, B * H, N, d, causal, softmax_scale, lay, s);
-  if (e != hipSuccess) return ATTN_ERR_LAUNCH;
-  e = attn_bwd_dq_dispatch(Q, K, V, dO, LSE, delta, dQ, B * H, N, d, causal, softmax_scale, lay, s);
   return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 

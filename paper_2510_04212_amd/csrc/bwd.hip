@@ -1,7 +1,8 @@
 // Flash-attention backward for gfx950 (Alg. 2 of arXiv 2510.04212), as two kernels so that no
 // gradient needs a cross-work-group reduction (no atomics, deterministic):
 //
-//   attn_bwd_dkdv_kernel  one work-group per (batch, head, 128-key block); K_j / V_j fragments
+//   attn_bwd_dkdv_kernel  one work-group per (batch, head, 128-key block) -- under the causal mask
+//                         per pair of mirrored blocks, one after the other; K_j / V_j fragments
 //                         stay in registers, query tiles (Q_i, dO_i, L_i, delta_i; 64 rows) stream
 //                         through LDS.  Per tile:  S = Q_i K_j^T,  P = exp(S - L),  dP = dO_i V_j^T,
 //                         dS = P o (dP - delta),  dV_j^T += dO_i^T P,  dK_j^T += Q_i^T dS.
@@ -355,14 +356,26 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
   }
 }
 
-// DELTA_MODE: instead of dQ the kernel forms delta = rowsum(P o dP) (the recomputed,
-// float32 form of delta of Sec. 3.2: mathematically rowsum(dO o O), but free of the forward's
-// bf16 roundings of O); `delta` is not read, `delta_out` receives the result, dQ is not touched.
-template <int D, bool CAUSAL, bool RAGGED, bool DELTA_MODE>
+// MODE of the dQ kernel:
+//   kGivenDelta     delta is read from `delta` (Alg. 2 with delta computed by attn_delta);
+//   kRecomputeDelta instead of dQ the kernel forms delta = rowsum(P o dP) (the recomputed,
+//                   float32 form of delta of Sec. 3.2: mathematically rowsum(dO o O), but free of the
+//                   forward's bf16 roundings of O); `delta` is not read, `delta_out` receives the
+//                   result, dQ is not touched;
+//   kOwnDelta       the kernel forms delta = rowsum(dO o O) (Alg. 2 step 4) itself, for the rows it
+//                   holds anyway, from `O`, writes it to `delta_out` for the dK/dV kernel that
+//                   follows, and goes on as kGivenDelta.  The sum is taken in the order of the
+//                   stand-alone delta kernel (8-element chains per 16-byte chunk, then a binary tree
+//                   over chunks at distances D/16 ... 1), so both give the same bits.
+constexpr int kGivenDelta = 0, kRecomputeDelta = 1, kOwnDelta = 2;
+
+template <int D, bool CAUSAL, bool RAGGED, int MODE>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
-    bf16_t* __restrict__ dQ, float* __restrict__ delta_out, int N, float alpha, Layout lay) {
+    const bf16_t* __restrict__ O, bf16_t* __restrict__ dQ, float* __restrict__ delta_out, int N,
+    float alpha, Layout lay) {
+  constexpr bool DELTA_MODE = MODE == kRecomputeDelta;
   constexpr int TILE_BYTES = kKTile * D * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* ldsK = smem;
@@ -397,7 +410,28 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
   }
   float l2 = LSE[(size_t)bh * N + qc] * kLog2e;
   if (RAGGED && l2 == -INFINITY) l2 = 0.f;             // a query that sees no key: all its scores are masked below
-  const float dl = DELTA_MODE ? 0.f : delta[(size_t)bh * N + qc];
+  float dl = 0.f;
+  if (MODE == kGivenDelta) dl = delta[(size_t)bh * N + qc];
+  if (MODE == kOwnDelta) {
+    // this lane holds chunks 2kc + h of its row: the chains of its chunks, the tree levels that
+    // stay inside one parity class, and the last level (chunk 0 + chunk 1 classes) across the
+    // two lanes of the row
+    float cs[D / 16];
+#pragma unroll
+    for (int kc = 0; kc < D / 16; ++kc) {
+      const bf16x8 o8 = *reinterpret_cast<const bf16x8*>(O + head_off + (size_t)qc * sn + 16 * kc + 8 * h);
+      float c = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) c = __builtin_fmaf((float)o8[e], (float)dof[kc][e], c);
+      cs[kc] = c;
+    }
+#pragma unroll
+    for (int off = D / 32; off >= 1; off >>= 1)
+#pragma unroll
+      for (int kc = 0; kc < off; ++kc) cs[kc] += cs[kc + off];
+    dl = sum_with_partner32(cs[0]);
+    if (h == 0 && (!RAGGED || qw + r < N)) delta_out[(size_t)bh * N + qw + r] = dl;
+  }
   float pdp = 0.f;                                   // DELTA_MODE: this lane's share of sum_k P dP
   // -delta_i in all 16 accumulator slots of the lane: the third operand of the first dP^T matrix
   // instruction of every key block, which then delivers dP - delta with no vector instruction
@@ -521,18 +555,18 @@ static hipError_t launch_dkdv(const void* Q, const void* K, const void* V, const
   return hipGetLastError();
 }
 
-template <int D, bool CAUSAL, bool RAGGED, bool DELTA_MODE>
+template <int D, bool CAUSAL, bool RAGGED, int MODE>
 static hipError_t launch_dq(const void* Q, const void* K, const void* V, const void* dO,
-                            const float* LSE, const float* delta, void* dQ, float* delta_out,
-                            int BH, int N, float alpha, Layout lay, hipStream_t st) {
+                            const float* LSE, const float* delta, const void* O, void* dQ,
+                            float* delta_out, int BH, int N, float alpha, Layout lay, hipStream_t st) {
   constexpr int smem = 4 * kKTile * D * 2;
   static bool set = false;
-  auto k = attn_bwd_dq_kernel<D, CAUSAL, RAGGED, DELTA_MODE>;
+  auto k = attn_bwd_dq_kernel<D, CAUSAL, RAGGED, MODE>;
   hipError_t e;
   if ((e = set_smem(k, smem, set)) != hipSuccess) return e;
   hipLaunchKernelGGL(k, dim3(BH * ((N + kQPerWG - 1) / kQPerWG)), dim3(256), smem, st, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
-                     (bf16_t*)dQ, delta_out, N, alpha, lay);
+                     (const bf16_t*)O, (bf16_t*)dQ, delta_out, N, alpha, lay);
   return hipGetLastError();
 }
 
@@ -560,13 +594,18 @@ hipError_t attn_bwd_dkdv_dispatch(const void* Q, const void* K, const void* V, c
   return hipErrorInvalidValue;
 }
 
+// O == nullptr: delta is given.  Otherwise delta is formed by the kernel from O and dO and also
+// written to delta_out (which must then be non-null).
 hipError_t attn_bwd_dq_dispatch(const void* Q, const void* K, const void* V, const void* dO,
-                                const float* LSE, const float* delta, void* dQ, int BH, int N,
-                                int d, int causal, float alpha, Layout lay, hipStream_t st) {
+                                const float* LSE, const float* delta, const void* O, void* dQ,
+                                float* delta_out, int BH, int N, int d, int causal, float alpha,
+                                Layout lay, hipStream_t st) {
   const bool ragged = (N % kQPerWG) != 0 || lay.Nk != N;
+  const bool own = O != nullptr;
 #define CASE(DD, CC, RR)                                                \
   if (d == DD && (causal != 0) == CC && ragged == RR)                   \
-    return launch_dq<DD, CC, RR, false>(Q, K, V, dO, LSE, delta, dQ, nullptr, BH, N, alpha, lay, st);
+    return own ? launch_dq<DD, CC, RR, kOwnDelta>(Q, K, V, dO, LSE, nullptr, O, dQ, delta_out, BH, N, alpha, lay, st) \
+               : launch_dq<DD, CC, RR, kGivenDelta>(Q, K, V, dO, LSE, delta, nullptr, dQ, nullptr, BH, N, alpha, lay, st);
   CASE(64, false, false) CASE(64, false, true) CASE(64, true, false) CASE(64, true, true)
   CASE(128, false, false) CASE(128, false, true) CASE(128, true, false) CASE(128, true, true)
 #undef CASE
@@ -580,7 +619,7 @@ hipError_t attn_delta_recompute_dispatch(const void* Q, const void* K, const voi
                                          Layout lay, hipStream_t st) {
 #define CASE(DD, CC)                                  \
   if (d == DD && (causal != 0) == CC)                 \
-    return launch_dq<DD, CC, true, true>(Q, K, V, dO, LSE, nullptr, nullptr, delta_out, BH, N, alpha, lay, st);
+    return launch_dq<DD, CC, true, kRecomputeDelta>(Q, K, V, dO, LSE, nullptr, nullptr, nullptr, delta_out, BH, N, alpha, lay, st);
   CASE(64, false) CASE(64, true) CASE(128, false) CASE(128, true)
 #undef CASE
   return hipErrorInvalidValue;

@@ -413,3 +413,25 @@ def test_matrix_clock_probe(lib):
     assert raw.attn_probe_matrix_clock(out.data_ptr(), 0, 10, None) == 2
     assert raw.attn_probe_matrix_clock(out.data_ptr(), 8, 0, None) == 2
     assert raw.attn_probe_matrix_clock(None, 8, 10, None) == 1
+
+
+@pytest.mark.parametrize("B,H,N,d,causal", [(1, 2, 128, 64, True), (2, 2, 384, 128, True), (1, 3, 200, 64, False),
+                                             (1, 2, 333, 128, True), (1, 1, 1, 64, True), (1, 2, 1024, 128, False)])
+def test_dq_stage_forming_its_own_delta_gives_the_same_bits(lib, B, H, N, d, causal):
+    """attn_bwd_dq_delta == attn_delta followed by attn_bwd_dq, bit for bit (delta and dQ), and
+    attn_bwd (which uses it) == the three separate stages."""
+    g = torch.Generator().manual_seed(N + d)
+    x = {k: torch.randn((B, H, N, d), generator=g).to(torch.bfloat16).to(DEV) for k in ("Q", "K", "V", "dO")}
+    alpha = d ** -0.5
+    O, L = lib.attn_fwd(x["Q"], x["K"], x["V"], causal, alpha, lib.MITIGATED)
+    delta = lib.attn_delta(O, x["dO"])
+    dQ = lib.attn_bwd_dq(x["Q"], x["K"], x["V"], x["dO"], L, delta, causal, alpha)
+    dK, dV = lib.attn_bwd_dkdv(x["Q"], x["K"], x["V"], x["dO"], L, delta, causal, alpha)
+    dQ2, delta2 = lib.attn_bwd_dq_delta(x["Q"], x["K"], x["V"], O, x["dO"], L, causal, alpha)
+    torch.cuda.synchronize()
+    assert torch.equal(delta, delta2) and torch.equal(dQ, dQ2)
+    ws = torch.empty(max(256, lib.bwd_workspace_bytes(B, H, N, d)), dtype=torch.uint8, device=DEV)
+    dQ3, dK3, dV3 = lib.attn_bwd(x["Q"], x["K"], x["V"], O, x["dO"], L, causal, alpha, lib.MITIGATED, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dQ3, dQ) and torch.equal(dK3, dK) and torch.equal(dV3, dV)
+    assert torch.equal(ws[: B * H * N * 4].view(torch.float32).view(B, H, N), delta)

@@ -92,6 +92,11 @@ def test_argument_validation_happens_on_the_host(binding):
     assert lib.attn_fwd_rect(None, None, None, None, None, 0, 4, 128, 256, 64, 1, 0.125, 0, 2.0, 1e-3, None) == OK
     br = lambda Nq, Nk, wb: lib.attn_bwd_rect(*ptrs_for_strided, ws_for_strided, wb, 1, 1, Nq, Nk, 64, 1, 0.125, 0, None)
     assert br(128, 0, 4096) == UNSUP and br(200, 64, 512) == WS     # delta has Nq = 200 floats: 1024 bytes
+    dqd = lambda *a: lib.attn_bwd_dq_delta(*a, 1, 1, 128, 64, 1, 0.125, None)
+    pp = [ctypes.c_void_p(0x1000 * (i + 1)) for i in range(8)]
+    assert dqd(*pp[:7], None) == NULL and dqd(*pp[:6], pp[0], pp[7]) == BAD      # dQ aliases Q
+    assert dqd(*pp[:6], pp[6], pp[6]) == BAD and dqd(*pp[:6], pp[6], pp[3]) == BAD   # delta aliases dQ / O
+    assert lib.attn_bwd_dq_delta(*([None] * 8), 0, 2, 128, 64, 1, 0.125, None) == OK
     rc = lambda *a: lib.attn_delta_recompute(*a, 1, 1, 128, 64, 1, 0.125, None)
     assert rc(p, p, p, p, p, None) == NULL and rc(p, p, p, p, p, p) == BAD and rc(p, p, p, mis, p, q) == BAD
     assert lib.attn_delta_recompute(p, p, p, p, p, q, 1, 1, 128, 64, 1, -1.0, None) == BAD
