@@ -47,7 +47,7 @@ DEVI void store_acc_T(bf16_t* dst_row, const f32x16 (&acc)[D / 32], float scale,
 // GROUPED: grouped-query attention (lay.group > 1): the work-group serves several query heads.
 // Kept out of the ordinary kernel so that its tile loop has a fixed head and no bookkeeping.
 template <int D, bool CAUSAL, bool RAGGED, bool GROUPED>
-__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
+__global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, int N, float alpha, Layout lay) {
@@ -581,13 +581,14 @@ hipError_t attn_bwd_dkdv_dispatch(const void* Q, const void* K, const void* V, c
 #define CASEG(DD, CC)                                 \
   if (d == DD && (causal != 0) == CC)                 \
     return launch_dkdv<DD, CC, true, true>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, lay, st);
-    CASEG(64, false) CASEG(64, true) CASEG(128, false) CASEG(128, true)
+    CASEG(32, false) CASEG(32, true) CASEG(64, false) CASEG(64, true) CASEG(128, false) CASEG(128, true)
 #undef CASEG
     return hipErrorInvalidValue;
   }
 #define CASE(DD, CC, RR)                                                \
   if (d == DD && (causal != 0) == CC && ragged == RR)                   \
     return launch_dkdv<DD, CC, RR, false>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, lay, st);
+  CASE(32, false, false) CASE(32, false, true) CASE(32, true, false) CASE(32, true, true)
   CASE(64, false, false) CASE(64, false, true) CASE(64, true, false) CASE(64, true, true)
   CASE(128, false, false) CASE(128, false, true) CASE(128, true, false) CASE(128, true, true)
 #undef CASE
@@ -606,6 +607,7 @@ hipError_t attn_bwd_dq_dispatch(const void* Q, const void* K, const void* V, con
   if (d == DD && (causal != 0) == CC && ragged == RR)                   \
     return own ? launch_dq<DD, CC, RR, kOwnDelta>(Q, K, V, dO, LSE, nullptr, O, dQ, delta_out, BH, N, alpha, lay, st) \
                : launch_dq<DD, CC, RR, kGivenDelta>(Q, K, V, dO, LSE, delta, nullptr, dQ, nullptr, BH, N, alpha, lay, st);
+  CASE(32, false, false) CASE(32, false, true) CASE(32, true, false) CASE(32, true, true)
   CASE(64, false, false) CASE(64, false, true) CASE(64, true, false) CASE(64, true, true)
   CASE(128, false, false) CASE(128, false, true) CASE(128, true, false) CASE(128, true, true)
 #undef CASE
@@ -620,7 +622,7 @@ hipError_t attn_delta_recompute_dispatch(const void* Q, const void* K, const voi
 #define CASE(DD, CC)                                  \
   if (d == DD && (causal != 0) == CC)                 \
     return launch_dq<DD, CC, true, kRecomputeDelta>(Q, K, V, dO, LSE, nullptr, nullptr, nullptr, delta_out, BH, N, alpha, lay, st);
-  CASE(64, false) CASE(64, true) CASE(128, false) CASE(128, true)
+  CASE(32, false) CASE(32, true) CASE(64, false) CASE(64, true) CASE(128, false) CASE(128, true)
 #undef CASE
   return hipErrorInvalidValue;
 }

@@ -35,6 +35,9 @@ DEVI f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // x 64 bytes both spread over all 64 LDS banks.
 template <int D> DEVI int swz(int row);
 template <> DEVI int swz<128>(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+// D = 32: a row is 4 chunks (64 bytes), four consecutive rows span the 64 banks once; rows r and
+// r + 4 would collide in (a) unless their chunk positions differ.  (b) touches 8 whole rows there.
+template <> DEVI int swz<32>(int row) { return (row >> 2) & 3; }
 template <> DEVI int swz<64>(int row) {
   int t = row >> 1;
   return ((t & 1) << 2) | (t & 2) | ((t >> 2) & 1);
@@ -250,8 +253,9 @@ DEVI float add_pair_bf16(bf16x2 p, float acc) {
 // each fed by PER LDS fragment reads: the reads are issued AHEAD matrix instructions before
 // their use, so that LDS latency is covered by matrix-core work instead of stalling the wave.
 // (sched_group_barrier masks: 0x008 = MFMA, 0x100 = LDS read.)
-template <int N, int PER, int AHEAD> DEVI void sched_reads_ahead_of_mfma() {
+template <int N, int PER, int AHEAD_> DEVI void sched_reads_ahead_of_mfma() {
   static_assert(PER == 1 || PER == 2, "PER");
+  constexpr int AHEAD = AHEAD_ < N ? AHEAD_ : N;
   __builtin_amdgcn_sched_group_barrier(0x100, AHEAD * PER, 0);
 #pragma unroll
   for (int i = 0; i < N - AHEAD; ++i) {

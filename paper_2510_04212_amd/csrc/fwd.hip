@@ -299,7 +299,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
 
 }  // namespace
 
-extern "C" int attn_fwd_key_tile(int d) { return (d == 64 || d == 128) ? kBc : 0; }
+extern "C" int attn_fwd_key_tile(int d) { return (d == 32 || d == 64 || d == 128) ? kBc : 0; }
 
 template <int D, bool CAUSAL, int VARIANT, bool RAGGED, bool EXTRAS>
 static hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
@@ -336,7 +336,7 @@ hipError_t attn_fwd_dispatch(const void* Q, const void* K, const void* V, void* 
     if (e != hipSuccess) return e;                                                               \
     return launch_fwd<DD, CC, kFixedNorm, true, true>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, lay, st); \
   }
-    CASE2(64, false) CASE2(64, true) CASE2(128, false) CASE2(128, true)
+    CASE2(32, false) CASE2(32, true) CASE2(64, false) CASE2(64, true) CASE2(128, false) CASE2(128, true)
 #undef CASE2
     return hipErrorInvalidValue;
   }
@@ -346,6 +346,7 @@ hipError_t attn_fwd_dispatch(const void* Q, const void* K, const void* V, void* 
     return (N % kBr || lay.Nk != N) ? launch_fwd<DD, CC, VV, true, false>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, lay, st) \
                      : launch_fwd<DD, CC, VV, false, false>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, lay, st); \
   }
+  CASE(32, false, 0) CASE(32, false, 1) CASE(32, true, 0) CASE(32, true, 1)
   CASE(64, false, 0) CASE(64, false, 1) CASE(64, true, 0) CASE(64, true, 1)
   CASE(128, false, 0) CASE(128, false, 1) CASE(128, true, 0) CASE(128, true, 1)
 #undef CASE

@@ -101,7 +101,7 @@ def test_argument_validation_happens_on_the_host(binding):
     assert rc(p, p, p, p, p, None) == NULL and rc(p, p, p, p, p, p) == BAD and rc(p, p, p, mis, p, q) == BAD
     assert lib.attn_delta_recompute(p, p, p, p, p, q, 1, 1, 128, 64, 1, -1.0, None) == BAD
     assert lib.attn_delta(None, p, p, 1, 1, 128, 64, None) == NULL
-    assert lib.attn_delta(p, p, p, 1, 1, 130, 32, None) == UNSUP
+    assert lib.attn_delta(p, p, p, 1, 1, 130, 48, None) == UNSUP
     assert lib.attn_delta(None, None, None, 2, 0, 128, 64, None) == OK
     ptrs = [ctypes.c_void_p(0x1000 * (i + 1)) for i in range(9)]
     ws = ctypes.c_void_p(0x100000)
