@@ -39,7 +39,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="mid", help="mid | long | gpt2s | tied | pairs_skew | tiny")
+    ap.add_argument("--workload", default="mid", help="mid | long | long_full | gpt2s | tied | pairs_skew | tiny")
     ap.add_argument("--variant", default="mitigated", choices=["standard", "mitigated", "mitigated_row"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -200,13 +200,13 @@ def main():
 
     # the other two throughput workloads of the build target, same step, fewer repetitions
     also = {}
-    for name in ("gpt2s", "mid", "long"):
+    for name in ("gpt2s", "mid", "long", "long_full"):
         if name == w.name or args.only_headline:
             continue
         j2 = Job(synth.WORKLOADS[name])
         ms2, per2 = j2.timed(variant, max(5, args.steps // 2), 3)
         f2 = j2.w.flops_fwd_bwd()
-        also[name] = {"value": round(f2 / (ms2 * 1e-3) / 1e12, 2), "ms_per_step": round(ms2, 4),
+        also[name] = {"causal": j2.w.causal, "value": round(f2 / (ms2 * 1e-3) / 1e12, 2), "ms_per_step": round(ms2, 4),
                       "frac_of_bf16_peak": round(f2 / (ms2 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
                       "kernel_ms": {k: round(v, 4) for k, v in per2.items()}}
         del j2

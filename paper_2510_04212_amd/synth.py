@@ -77,6 +77,8 @@ WORKLOADS = {
     "mid": Workload("mid", 4, 32, 4096, 128, True, 1004),
     # long context, sharp attention
     "long": Workload("long", 1, 16, 16384, 128, True, 1005, qk_scale=2.0),
+    # the same without the causal mask (every work-group carries the same load, no diagonal tiles)
+    "long_full": Workload("long_full", 1, 16, 16384, 128, False, 1005, qk_scale=2.0),
 }
 
 _TENSOR_ID = {"Q": 0, "K": 1, "V": 2, "dO": 3, "aux": 4}
