@@ -42,6 +42,7 @@ from typing import Callable
 import numpy as np
 
 from .bf16 import round_to_bf16
+from .fp8 import round_to_e4m3
 
 STANDARD = 0    # Alg. 1
 MITIGATED = 1   # Alg. 3
@@ -52,10 +53,17 @@ class Precision:
     name: str
     dtype: type
     rnd: Callable
+    rnd_pv: Callable = None     # rounding of the two operands of the P-bar V product, if not `rnd`
 
 
 FP64 = Precision("fp64", np.float64, lambda x: x)
 BF16 = Precision("bf16", np.float32, round_to_bf16)
+# The BF16 dataflow with the one product the paper's analysis singles out, P-bar V (Sec. 3.3.2),
+# taken in 8-bit floating point: P-bar and V are rounded to E4M3 (rounding point (r1) moves to that
+# format, V is quantised without a scale factor), the products are summed in binary32, and
+# everything downstream -- (r2) the row sum of the rounded P-bar, (r3), (r4) -- is unchanged.
+# Forward only; an exploration of the paper's future-work remark on FP8, not something it specifies.
+BF16_PV_E4M3 = Precision("bf16, P-bar V in e4m3", np.float32, round_to_bf16, round_to_e4m3)
 
 
 def _tile_scores(Qw, Kj, alpha, causal, k0, prec, shift=0):
@@ -116,7 +124,10 @@ def forward(Q, K, V, alpha, causal, variant=STANDARD, beta=2.0, eps=1e-3, Bc=Non
             # rows with nothing visible yet have m_new = -inf: they contribute nothing
             safe_m = np.where(np.isneginf(m_new), dt(0.0), m_new)
             Pbar = np.exp(S - safe_m[:, None]).astype(dt)                 # step 7
-            Phat = prec.rnd(Pbar).astype(dt)                              # (r1)
+            rnd_pv = prec.rnd_pv or prec.rnd
+            Phat = rnd_pv(Pbar).astype(dt)                                # (r1)
+            if prec.rnd_pv is not None:
+                Vj = prec.rnd_pv(Vj).astype(dt)
             corr = np.where(np.isneginf(m), dt(0.0), np.exp(m - safe_m)).astype(dt)
             ell = (corr * ell + np.sum(Phat, axis=1, dtype=dt)).astype(dt)   # step 7, (r2)
             acc = (corr[:, None] * acc + Phat @ Vj).astype(dt)            # step 8

@@ -266,3 +266,28 @@ def test_degenerate_cases():
     assert f["ell"][0] == 0 and np.isnan(f["O"]).all()
     f = flash.forward(Q, K, V, 1.0, False, flash.STANDARD)
     assert np.isfinite(f["O"]).all()
+
+
+def test_fp8_product_mode_only_touches_the_two_operands_of_pbar_v():
+    """BF16_PV_E4M3 against a hand-rolled single-tile evaluation of the same dataflow; with values
+    that E4M3 represents exactly it coincides with the bf16 mode."""
+    from oracle.fp8 import round_to_e4m3
+    rng = np.random.default_rng(21)
+    N, d = 24, 8
+    Q, K, V = [round_to_bf16(rng.standard_normal((N, d)).astype(np.float32)) for _ in range(3)]
+    f = flash.forward(Q, K, V, 0.4, True, flash.STANDARD, prec=flash.BF16_PV_E4M3)
+    S = exact.scores(Q, K, 0.4, True).astype(np.float32)
+    m = S.max(axis=1)
+    P8 = round_to_e4m3(np.exp(S - m[:, None]).astype(np.float32))
+    acc = (P8.astype(np.float64) @ round_to_e4m3(V).astype(np.float64))       # products of two 4-bit significands: exact
+    ell = P8.sum(axis=1, dtype=np.float32)
+    O = round_to_bf16(round_to_bf16(acc.astype(np.float32)) / ell[:, None])
+    assert np.array_equal(f["O"], O)
+    assert np.allclose(f["L"], m + np.log(ell), rtol=1e-6)
+    assert (f["ones"] >= 1).all()
+    # every value a power of two or 1.5 times one: both formats hold them exactly
+    V2 = (2.0 ** rng.integers(-3, 3, size=(N, d)) * rng.choice([1.0, 1.5, -1.0], size=(N, d))).astype(np.float32)
+    K2 = np.zeros((N, d), dtype=np.float32)          # all scores equal: P-bar = 1 everywhere
+    a = flash.forward(Q, K2, V2, 0.4, True, flash.STANDARD, prec=flash.BF16_PV_E4M3)
+    b = flash.forward(Q, K2, V2, 0.4, True, flash.STANDARD, prec=flash.BF16)
+    assert np.array_equal(a["O"], b["O"])
