@@ -272,6 +272,7 @@ def test_fp8_product_mode_only_touches_the_two_operands_of_pbar_v():
     """BF16_PV_E4M3 against a hand-rolled single-tile evaluation of the same dataflow; with values
     that E4M3 represents exactly it coincides with the bf16 mode."""
     from oracle.fp8 import round_to_e4m3
+    from oracle.bf16 import round_to_bf16
     rng = np.random.default_rng(21)
     N, d = 24, 8
     Q, K, V = [round_to_bf16(rng.standard_normal((N, d)).astype(np.float32)) for _ in range(3)]
