@@ -105,10 +105,18 @@ int attn_fwd_ex(const void* Q, const void* K, const void* V, void* O, float* LSE
  *                standard variant).
  *   flags        ATTN_FWD_SINGLE_ROUNDING: the unnormalised output is NOT rounded to bf16 before
  *                the division by l ("computing only O-bar = P-bar V in FP32", Sec. 3.3.2); O is
- *                still stored as bf16.  Other bits: ATTN_ERR_BAD_ARG.
+ *                still stored as bf16.
+ *                ATTN_FWD_PV_E4M3: an exploration beyond the paper (its closing remark on FP8):
+ *                the P-bar V product takes both operands in the 8-bit format E4M3 -- P-bar is
+ *                rounded to E4M3 instead of bf16, V is quantised to E4M3 without a scale
+ *                factor -- on the FP8 matrix instruction, sums in float32; the row sum l is of
+ *                the rounded P-bar, ones_count counts its unit entries, everything else is
+ *                unchanged.  The backward pass has no such mode.
+ *                Other bits: ATTN_ERR_BAD_ARG.
  * Optional pointers must be 16-byte aligned and must not alias any other argument.
  */
 #define ATTN_FWD_SINGLE_ROUNDING 1u
+#define ATTN_FWD_PV_E4M3 2u
 int attn_fwd_opt(const void* Q, const void* K, const void* V, void* O, float* LSE,
                  float* O_hp, int* ones_count, int* fired_count,
                  int B, int H, int N, int d, int causal, float softmax_scale, int variant,

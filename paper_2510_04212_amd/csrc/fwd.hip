@@ -25,7 +25,18 @@ struct FwdExtras {
   int* ones;            // [B,H,N]: number of keys whose rounded P-bar was exactly 1, or null
   int* fired;           // [B,H,N]: number of key tiles in which Alg. 3 moved the normaliser, or null
   int single_rounding;  // nonzero: O-bar is NOT rounded to bf16 before the division by l
+  int pv_e4m3;          // nonzero: the P-bar V product takes both operands in 8-bit E4M3
 };
+
+// Eight float32 values -> eight E4M3 bytes (hardware conversion: round to nearest even).
+DEVI long pack_e4m3(const float (&v)[8]) {
+  int w0 = 0, w1 = 0;
+  w0 = __builtin_amdgcn_cvt_pk_fp8_f32(v[0], v[1], w0, false);
+  w0 = __builtin_amdgcn_cvt_pk_fp8_f32(v[2], v[3], w0, true);
+  w1 = __builtin_amdgcn_cvt_pk_fp8_f32(v[4], v[5], w1, false);
+  w1 = __builtin_amdgcn_cvt_pk_fp8_f32(v[6], v[7], w1, true);
+  return (long)(((unsigned long long)(unsigned)w1 << 32) | (unsigned)w0);
+}
 
 // VARIANT: 0 = Alg. 1, 1 = Alg. 3 (repeated maximum looked for inside each key tile, as the
 // algorithm is written), and the two passes of the tile-size-independent form of Alg. 3
@@ -200,6 +211,54 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
           m = m_new;
           mneg = unseen ? 0.f : -m_new * kLog2e;
         }
+        if (EXTRAS && ex.pv_e4m3 != 0) {
+          // ---- exploration beyond the paper (its future-work remark on FP8): the same step with
+          // P-bar and V_j rounded to E4M3 and multiplied by the FP8 matrix instruction; the row sum
+          // is of the rounded P-bar, everything downstream is unchanged.  Same k-slot order in
+          // both operands as in the bf16 path.
+          long pf8[2][2];
+          float psum8 = 0.f;
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc) {
+              float pv[8];
+#pragma unroll
+              for (int jj = 0; jj < 8; ++jj)
+                pv[jj] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][8 * cc + jj], c2, mneg));
+              const long pk = pack_e4m3(pv);
+              pf8[kb][cc] = pk;
+              const int w0 = (int)(unsigned)pk, w1 = (int)(unsigned)((unsigned long long)pk >> 32);
+              const float back[8] = {__builtin_amdgcn_cvt_f32_fp8(w0, 0), __builtin_amdgcn_cvt_f32_fp8(w0, 1),
+                                     __builtin_amdgcn_cvt_f32_fp8(w0, 2), __builtin_amdgcn_cvt_f32_fp8(w0, 3),
+                                     __builtin_amdgcn_cvt_f32_fp8(w1, 0), __builtin_amdgcn_cvt_f32_fp8(w1, 1),
+                                     __builtin_amdgcn_cvt_f32_fp8(w1, 2), __builtin_amdgcn_cvt_f32_fp8(w1, 3)};
+#pragma unroll
+              for (int jj = 0; jj < 8; ++jj) {
+                psum8 += back[jj];
+                ones_cnt += back[jj] == 1.0f ? 1 : 0;
+              }
+            }
+          lsum = lsum * corr + psum8;
+          if (VARIANT != kFixedNorm && __builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+              for (int i = 0; i < 16; ++i) acc[db][i] *= corr;
+          }
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+              for (int db = 0; db < D / 32; ++db) {
+                const bf16x8 v8 = lds_col8<D>(tV, fo, 32 * kb + 16 * cc, db);
+                float vv[8];
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj) vv[jj] = (float)v8[jj];
+                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(pack_e4m3(vv), pf8[kb][cc], acc[db], 0, 0, 0);
+              }
+        } else {
         // ---- P-bar = exp(S - m), rounded to bf16; row sum of the ROUNDED values
         bf16x8 pf[2][2];
         float psum = 0.f;
@@ -233,6 +292,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
 #pragma unroll
             for (int db = 0; db < D / 32; ++db)
               acc[db] = mfma32(lds_col8<D>(tV, fo, 32 * kb + 16 * cc, db), pf[kb][cc], acc[db]);
+        }
       }
     }
     wait_vmem();
@@ -326,9 +386,10 @@ static hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* 
 hipError_t attn_fwd_dispatch(const void* Q, const void* K, const void* V, void* O, float* LSE,
                              int BH, int N, int d, int causal, float alpha, int variant,
                              float beta, float eps, float* O_hp, int* ones, int* fired,
-                             int single_rounding, Layout lay, hipStream_t st) {
-  const bool extras = O_hp != nullptr || ones != nullptr || fired != nullptr || single_rounding != 0;
-  const FwdExtras ex{O_hp, ones, fired, single_rounding};
+                             int flags, Layout lay, hipStream_t st) {
+  // flags: bit 0 = single rounding of the output, bit 1 = P-bar V in E4M3
+  const bool extras = O_hp != nullptr || ones != nullptr || fired != nullptr || flags != 0;
+  const FwdExtras ex{O_hp, ones, fired, flags & 1, (flags >> 1) & 1};
   if (variant == 2) {   // whole-row detection: statistics pass, then the fixed-normaliser pass
 #define CASE2(DD, CC)                                                                           \
   if (d == DD && (causal != 0) == CC) {                                                          \
