@@ -30,11 +30,11 @@ constexpr int kQTile = 64;        // dK/dV kernel: query rows per streamed tile
 constexpr int kQPerWG = 128;      // dQ kernel: queries per work-group (32 per wave)
 constexpr int kKTile = 64;        // dQ kernel: key rows per streamed tile
 
-template <int D>
-DEVI void store_acc_T(bf16_t* dst_row, const f32x16 (&acc)[D / 32], float scale, int h) {
+template <int NDB>
+DEVI void store_acc_T(bf16_t* dst_row, const f32x16 (&acc)[NDB], float scale, int h) {
   // acc[db][i] = X^T[d = 32db + 8(i/4) + 4h + (i%4)][row of this lane]; 4 consecutive d -> 8 bytes
 #pragma unroll
-  for (int db = 0; db < D / 32; ++db)
+  for (int db = 0; db < NDB; ++db)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       bf16x4 o4;
@@ -46,6 +46,12 @@ DEVI void store_acc_T(bf16_t* dst_row, const f32x16 (&acc)[D / 32], float scale,
 
 // GROUPED: grouped-query attention (lay.group > 1): the work-group serves several query heads.
 // Kept out of the ordinary kernel so that its tile loop has a fixed head and no bookkeeping.
+// At D = 256 the two accumulator sets of a full key block would not fit the register file next
+// to the K / V fragments: a work-group then owns 128 of the 256 columns of dK and dV (kDSplit
+// work-groups per key block, each recomputing S and dP), and the four-phase pipeline, whose
+// phases assume as many update as score instructions, is not used.
+template <int D> constexpr int kDSplit = D > 128 ? 2 : 1;
+
 template <int D, bool CAUSAL, bool RAGGED, bool GROUPED>
 __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
@@ -72,8 +78,12 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
   // Under the causal mask key block kt meets nkt - kt query blocks' worth of tiles: a work-group
   // takes block kt and then its mirror image nkt - 1 - kt, so that all work-groups carry the same
   // load (and there are half as many to start and drain).
-  const int npw = CAUSAL ? (nkt + 1) / 2 : nkt;        // work-groups per key/value head
-  const int wg = xcd_remap(blockIdx.x, gridDim.x);
+  const int npw = CAUSAL ? (nkt + 1) / 2 : nkt;        // work-groups per key/value head and column part
+  constexpr int DS = kDSplit<D>;
+  constexpr int NDB = D / 32 / DS;                     // 32-column blocks of dK / dV this work-group owns
+  const int wg_all = xcd_remap(blockIdx.x, gridDim.x);
+  const int db0 = (DS > 1) ? (wg_all % DS) * NDB : 0;  // first of them
+  const int wg = wg_all / DS;
   // with grouped queries a work-group serves the `group` query heads that share its key/value
   // head, one after the other
   const int bhk = wg / npw;
@@ -86,6 +96,16 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
   const float c2 = alpha * kLog2e;
   FragOffsets<D> fo;
   init_frag_offsets<D>(fo, lane);
+  // Transposing reads of the update products address column block db0 + db: a column block only
+  // enters the offset through chunk bits the swizzle leaves alone, so shifting by db0 blocks is one
+  // XOR per offset (32 columns = 4 chunks = 64 bytes).
+  FragOffsets<D> fo_upd = fo;
+  if (DS > 1) {
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db) fo_upd.col[half][db] ^= 64 * db0;
+  }
   TileLoader<D> loader;
   loader.init(tid, sn);
 
@@ -104,9 +124,9 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
       kf[kc] = *reinterpret_cast<const bf16x8*>(K + head_off + (size_t)keyc * sn + 16 * kc + 8 * h);
       vf[kc] = *reinterpret_cast<const bf16x8*>(V + head_off + (size_t)keyc * sn + 16 * kc + 8 * h);
     }
-    f32x16 dVt[D / 32], dKt[D / 32];
+    f32x16 dVt[NDB], dKt[NDB];
 #pragma unroll
-    for (int db = 0; db < D / 32; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
       for (int i = 0; i < 16; ++i) { dVt[db][i] = 0.f; dKt[db][i] = 0.f; }
 
@@ -115,8 +135,8 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
     const int nt = RAGGED ? (N + kQTile - 1) / kQTile : N / kQTile;
     if (RAGGED && t0 >= nt) {                        // no query sees these keys (more keys than queries reach): zero gradients
       if (kw + r < NK) {
-        store_acc_T<D>(dV + head_off + (size_t)(kw + r) * sn, dVt, 1.0f, h);
-        store_acc_T<D>(dK + head_off + (size_t)(kw + r) * sn, dKt, alpha, h);
+        store_acc_T<NDB>(dV + 32 * db0 + head_off + (size_t)(kw + r) * sn, dVt, 1.0f, h);
+        store_acc_T<NDB>(dK + 32 * db0 + head_off + (size_t)(kw + r) * sn, dKt, alpha, h);
       }
       continue;
     }
@@ -217,11 +237,11 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
 #pragma unroll
         for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
-          for (int db = 0; db < D / 32; ++db) {
-            dVt[db] = mfma32(lds_col8<D>(tdO, fo, 32 * qb + 16 * cc, db), pf[cc], dVt[db]);
-            dKt[db] = mfma32(lds_col8<D>(tQ, fo, 32 * qb + 16 * cc, db), dsf[cc], dKt[db]);
+          for (int db = 0; db < NDB; ++db) {
+            dVt[db] = mfma32(lds_col8<D>(tdO, fo_upd, 32 * qb + 16 * cc, db), pf[cc], dVt[db]);
+            dKt[db] = mfma32(lds_col8<D>(tQ, fo_upd, 32 * qb + 16 * cc, db), dsf[cc], dKt[db]);
           }
-        sched_reads_ahead_of_mfma<D / 8, 2, 4>();
+        sched_reads_ahead_of_mfma<4 * NDB, 2, 4>();
       };
       // Both 32-query blocks of a tile that lies entirely below the diagonal for this wave, as one
       // software-pipelined sequence of 4 x NS "slots" (one matrix instruction each).  The phase
@@ -242,10 +262,11 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
         auto rd_sdp = [&](int qb, int sl) -> bf16x8 {
           return lds_row8<D>((sl & 1) ? tdO : tQ, fo, 32 * qb, sl >> 1);
         };
-        // slot s of a dV/dK phase: cc = s / (2 D/32), db = (s/2) % (D/32), even -> dV (dO_i^T), odd -> dK (Q_i^T)
+        // slot s of a dV/dK phase: cc = s / (2 NDB), db = (s/2) % NDB, even -> dV (dO_i^T), odd -> dK (Q_i^T)
+        // (this path is only taken when the work-group owns all columns, NDB = D/32)
         auto rd_dvdk = [&](int qb, int sl) -> bf16x8 {
-          return lds_col8<D>((sl & 1) ? tQ : tdO, fo, 32 * qb + 16 * (sl / (2 * (D / 32))),
-                             (sl >> 1) % (D / 32));
+          return lds_col8<D>((sl & 1) ? tQ : tdO, fo_upd, 32 * qb + 16 * ((sl / (2 * NDB)) & 1),
+                             (sl >> 1) % NDB);
         };
         f32x16 s0, dp0, s1, dp1;
         bf16x8 pf0[2], dsf0[2], pf1[2], dsf1[2];
@@ -294,7 +315,7 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
 #pragma unroll
         for (int sl = 0; sl < NS; ++sl) {
           ring[(2 * NS + sl + AH) % R] = (sl + AH < NS) ? rd_dvdk(0, sl + AH) : rd_dvdk(1, sl + AH - NS);
-          const int cc = sl / (2 * (D / 32)), db = (sl >> 1) % (D / 32);
+          const int cc = (sl / (2 * NDB)) & 1, db = (sl >> 1) % NDB;
           if (sl & 1) dKt[db] = mfma32(ring[(2 * NS + sl) % R], dsf0[cc], dKt[db]);
           else dVt[db] = mfma32(ring[(2 * NS + sl) % R], pf0[cc], dVt[db]);
 #pragma unroll
@@ -311,13 +332,13 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
 #pragma unroll
         for (int sl = 0; sl < NS; ++sl) {
           if (sl + AH < NS) ring[(3 * NS + sl + AH) % R] = rd_dvdk(1, sl + AH);
-          const int cc = sl / (2 * (D / 32)), db = (sl >> 1) % (D / 32);
+          const int cc = (sl / (2 * NDB)) & 1, db = (sl >> 1) % NDB;
           if (sl & 1) dKt[db] = mfma32(ring[(3 * NS + sl) % R], dsf1[cc], dKt[db]);
           else dVt[db] = mfma32(ring[(3 * NS + sl) % R], pf1[cc], dVt[db]);
           __builtin_amdgcn_sched_barrier(0);
         }
       };
-      if ((!CAUSAL || qt0 + shift >= kw + 31) && (!RAGGED || qt0 + kQTile <= N)) {
+      if (DS == 1 && (!CAUSAL || qt0 + shift >= kw + 31) && (!RAGGED || qt0 + kQTile <= N)) {
         tile_pipelined();
       } else {
 #pragma unroll
@@ -350,8 +371,8 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
       }
     }
     if (!RAGGED || kw + r < NK) {
-      store_acc_T<D>(dV + head_off + (size_t)(kw + r) * sn, dVt, 1.0f, h);
-      store_acc_T<D>(dK + head_off + (size_t)(kw + r) * sn, dKt, alpha, h);
+      store_acc_T<NDB>(dV + 32 * db0 + head_off + (size_t)(kw + r) * sn, dVt, 1.0f, h);
+      store_acc_T<NDB>(dK + 32 * db0 + head_off + (size_t)(kw + r) * sn, dKt, alpha, h);
     }
   }
 }
@@ -370,7 +391,7 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
 constexpr int kGivenDelta = 0, kRecomputeDelta = 1, kOwnDelta = 2;
 
 template <int D, bool CAUSAL, bool RAGGED, int MODE>
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
+__global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const bf16_t* __restrict__ O, bf16_t* __restrict__ dQ, float* __restrict__ delta_out, int N,
@@ -527,7 +548,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     if (h == 0 && (!RAGGED || qw + r < N)) delta_out[(size_t)bh * N + qw + r] = dsum;
     return;
   }
-  if (!RAGGED || qw + r < N) store_acc_T<D>(dQ + head_off + (size_t)(qw + r) * sn, dQt, alpha, h);
+  if (!RAGGED || qw + r < N) store_acc_T<D / 32>(dQ + head_off + (size_t)(qw + r) * sn, dQt, alpha, h);
 }
 
 template <typename KernT>
@@ -549,7 +570,7 @@ static hipError_t launch_dkdv(const void* Q, const void* K, const void* V, const
   hipError_t e;
   if ((e = set_smem(k, smem, set)) != hipSuccess) return e;
   const int nkt = ((RAGGED ? lay.Nk : N) + kKeysPerWG - 1) / kKeysPerWG;
-  hipLaunchKernelGGL(k, dim3((BH / lay.group) * (CAUSAL ? (nkt + 1) / 2 : nkt)), dim3(256), smem, st, (const bf16_t*)Q,
+  hipLaunchKernelGGL(k, dim3((BH / lay.group) * (CAUSAL ? (nkt + 1) / 2 : nkt) * kDSplit<D>), dim3(256), smem, st, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
                      (bf16_t*)dK, (bf16_t*)dV, N, alpha, lay);
   return hipGetLastError();
@@ -582,6 +603,7 @@ hipError_t attn_bwd_dkdv_dispatch(const void* Q, const void* K, const void* V, c
   if (d == DD && (causal != 0) == CC)                 \
     return launch_dkdv<DD, CC, true, true>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, lay, st);
     CASEG(32, false) CASEG(32, true) CASEG(64, false) CASEG(64, true) CASEG(128, false) CASEG(128, true)
+    CASEG(256, false) CASEG(256, true)
 #undef CASEG
     return hipErrorInvalidValue;
   }
@@ -591,6 +613,7 @@ hipError_t attn_bwd_dkdv_dispatch(const void* Q, const void* K, const void* V, c
   CASE(32, false, false) CASE(32, false, true) CASE(32, true, false) CASE(32, true, true)
   CASE(64, false, false) CASE(64, false, true) CASE(64, true, false) CASE(64, true, true)
   CASE(128, false, false) CASE(128, false, true) CASE(128, true, false) CASE(128, true, true)
+  CASE(256, false, false) CASE(256, false, true) CASE(256, true, false) CASE(256, true, true)
 #undef CASE
   return hipErrorInvalidValue;
 }
@@ -610,6 +633,7 @@ hipError_t attn_bwd_dq_dispatch(const void* Q, const void* K, const void* V, con
   CASE(32, false, false) CASE(32, false, true) CASE(32, true, false) CASE(32, true, true)
   CASE(64, false, false) CASE(64, false, true) CASE(64, true, false) CASE(64, true, true)
   CASE(128, false, false) CASE(128, false, true) CASE(128, true, false) CASE(128, true, true)
+  CASE(256, false, false) CASE(256, false, true) CASE(256, true, false) CASE(256, true, true)
 #undef CASE
   return hipErrorInvalidValue;
 }
@@ -623,6 +647,7 @@ hipError_t attn_delta_recompute_dispatch(const void* Q, const void* K, const voi
   if (d == DD && (causal != 0) == CC)                 \
     return launch_dq<DD, CC, true, kRecomputeDelta>(Q, K, V, dO, LSE, nullptr, nullptr, nullptr, delta_out, BH, N, alpha, lay, st);
   CASE(32, false) CASE(32, true) CASE(64, false) CASE(64, true) CASE(128, false) CASE(128, true)
+  CASE(256, false) CASE(256, true)
 #undef CASE
   return hipErrorInvalidValue;
 }

@@ -35,6 +35,9 @@ DEVI f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // x 64 bytes both spread over all 64 LDS banks.
 template <int D> DEVI int swz(int row);
 template <> DEVI int swz<128>(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+// D = 256: rows are 512 bytes, as at D = 128 every row starts on bank 0: the same permutation of
+// the low four chunk-index bits serves (the fifth bit is left alone).
+template <> DEVI int swz<256>(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 // D = 32: a row is 4 chunks (64 bytes), four consecutive rows span the 64 banks once; rows r and
 // r + 4 would collide in (a) unless their chunk positions differ.  (b) touches 8 whole rows there.
 template <> DEVI int swz<32>(int row) { return (row >> 2) & 3; }

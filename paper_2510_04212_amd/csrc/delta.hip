@@ -72,13 +72,14 @@ hipError_t attn_delta_dispatch(const void* O, const void* dO, float* delta, long
                                int o_is_f32, Layout lay, hipStream_t st) {
   constexpr int UNROLL = 4;
   if (rows == 0) return hipSuccess;
-  if (d != 32 && d != 64 && d != 128) return hipErrorInvalidValue;
+  if (d != 32 && d != 64 && d != 128 && d != 256) return hipErrorInvalidValue;
   const int rpb = 256 / (d / 8) * UNROLL;
   dim3 grid((unsigned)((rows + rpb - 1) / rpb));
 #define LAUNCH(DD, HP)                                                                          \
   hipLaunchKernelGGL((attn_delta_kernel<DD, UNROLL, HP>), grid, dim3(256), 0, st, O,           \
                      (const bf16_t*)dO, delta, rows, N, lay)
-  if (d == 128) { if (o_is_f32) LAUNCH(128, true); else LAUNCH(128, false); }
+  if (d == 256) { if (o_is_f32) LAUNCH(256, true); else LAUNCH(256, false); }
+  else if (d == 128) { if (o_is_f32) LAUNCH(128, true); else LAUNCH(128, false); }
   else if (d == 64) { if (o_is_f32) LAUNCH(64, true); else LAUNCH(64, false); }
   else              { if (o_is_f32) LAUNCH(32, true); else LAUNCH(32, false); }
 #undef LAUNCH

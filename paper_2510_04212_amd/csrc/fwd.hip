@@ -49,7 +49,7 @@ DEVI long pack_e4m3(const float (&v)[8]) {
 constexpr int kRowStats = 3, kFixedNorm = 2;
 
 template <int D, bool CAUSAL, int VARIANT, bool RAGGED, bool EXTRAS>
-__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
+__global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_fwd_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, float* __restrict__ LSE, int N, float alpha, float beta, float eps,
     FwdExtras ex, Layout lay) {
@@ -359,7 +359,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
 
 }  // namespace
 
-extern "C" int attn_fwd_key_tile(int d) { return (d == 32 || d == 64 || d == 128) ? kBc : 0; }
+extern "C" int attn_fwd_key_tile(int d) { return (d == 32 || d == 64 || d == 128 || d == 256) ? kBc : 0; }
 
 template <int D, bool CAUSAL, int VARIANT, bool RAGGED, bool EXTRAS>
 static hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
@@ -398,6 +398,7 @@ hipError_t attn_fwd_dispatch(const void* Q, const void* K, const void* V, void* 
     return launch_fwd<DD, CC, kFixedNorm, true, true>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, lay, st); \
   }
     CASE2(32, false) CASE2(32, true) CASE2(64, false) CASE2(64, true) CASE2(128, false) CASE2(128, true)
+    CASE2(256, false) CASE2(256, true)
 #undef CASE2
     return hipErrorInvalidValue;
   }
@@ -410,6 +411,7 @@ hipError_t attn_fwd_dispatch(const void* Q, const void* K, const void* V, void* 
   CASE(32, false, 0) CASE(32, false, 1) CASE(32, true, 0) CASE(32, true, 1)
   CASE(64, false, 0) CASE(64, false, 1) CASE(64, true, 0) CASE(64, true, 1)
   CASE(128, false, 0) CASE(128, false, 1) CASE(128, true, 0) CASE(128, true, 1)
+  CASE(256, false, 0) CASE(256, false, 1) CASE(256, true, 0) CASE(256, true, 1)
 #undef CASE
   return hipErrorInvalidValue;
 }
