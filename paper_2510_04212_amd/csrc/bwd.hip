@@ -159,13 +159,18 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
       const int row = t * kQTile + (tid & (kQTile - 1));
       const int rowc = (RAGGED && row >= N) ? N - 1 : row;
       if (tid < kQTile) {
-        sreg = Lp[rowc] * kLog2e;
-        if (RAGGED && sreg == -INFINITY) sreg = 0.f;   // a query that sees no key: all its scores are masked below
-      } else if (tid < 2 * kQTile) sreg = -Dp[rowc];   // LDS holds -delta
+        sreg = Lp[rowc];
+      } else if (tid < 2 * kQTile) sreg = Dp[rowc];
+      // (The loaded values are not touched before store_stats: any arithmetic on them here would
+      // make the wave wait, at the start of the tile, for these loads and for the tile transfer
+      // issued just before them.)
     };
     auto store_stats = [&](int buf) {
-      if (tid < kQTile) ldsL[buf * kQTile + tid] = sreg;
-      else if (tid < 2 * kQTile) ldsD[buf * kQTile + tid - kQTile] = sreg;
+      if (tid < kQTile) {
+        float l = sreg * kLog2e;
+        if (RAGGED && l == -INFINITY) l = 0.f;         // a query that sees no key: all its scores are masked below
+        ldsL[buf * kQTile + tid] = l;
+      } else if (tid < 2 * kQTile) ldsD[buf * kQTile + tid - kQTile] = -sreg;   // LDS holds -delta
     };
     load_tile(Qh, dOh, Lh, Dh, t0, 0);
     store_stats(0);
