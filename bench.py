@@ -37,8 +37,8 @@ MEASURED_TRAFFIC_BYTES = {
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="mid", help="mid | long | long_full | gpt2s | tied | pairs_skew | tiny")
     ap.add_argument("--variant", default="mitigated", choices=["standard", "mitigated", "mitigated_row"])
     ap.add_argument("--no-cpu-baseline", action="store_true")

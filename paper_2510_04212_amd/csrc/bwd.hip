@@ -481,6 +481,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
   loader.template load_rows<RAGGED>(ldsK, Kh, 0, NK, tid);
   loader.template load_rows<RAGGED>(ldsV, Vh, 0, NK, tid);
   wait_vmem();
+#pragma unroll
+  for (int kc = 0; kc < D / 16; ++kc) { settle(qf[kc]); settle(dof[kc]); }
+  settle(l2);
   __syncthreads();
 
   for (int j = 0; j < ntiles; ++j) {

@@ -243,6 +243,14 @@ template <int D> struct TileLoader {
 // s_waitcnt vmcnt(0): every outstanding global load (including loads into LDS) has landed.
 DEVI void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
+// Marks a register value as used at this point, so that the compiler waits HERE for the load that
+// produces it rather than at its first real use.  The kernels call it on their register-resident
+// fragments right after the explicit wait in front of the tile loop: a compiler-generated
+// "vmcnt(n)" left inside the loop (needed in its first pass only) would in every later pass also
+// wait for the next tile's global->LDS transfers, which the compiler does not know of, and stall
+// the wave at the start of each tile until they have landed.
+template <class T> DEVI void settle(T& x) { asm volatile("" : "+v"(x)); }
+
 // Sum of the two bf16 values of a packed pair, added to acc in float32 (v_dot2c_f32_bf16 with
 // a (1,1) second operand).
 DEVI float add_pair_bf16(bf16x2 p, float acc) {

@@ -116,6 +116,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_fwd_kernel(
   const float inv_alpha = 1.0f / alpha;
 
   wait_vmem();
+#pragma unroll
+  for (int kc = 0; kc < D / 16; ++kc) settle(qf[kc]);
+  if (VARIANT == kFixedNorm) settle(m);
   __syncthreads();
 
   // One key tile; BUF (which LDS buffer holds it) is a compile-time constant so that every LDS
