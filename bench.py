@@ -27,10 +27,10 @@ PEAK_HBM_GBS = 8000.0
 # scaled by the same counter's reading for a 1 GiB device copy (see profiles/mid_hbm_traffic.txt).
 # Keyed by (workload, kernel); None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("mid", "fwd"): 539679534,
-    ("mid", "delta"): 270667480,
-    ("mid", "bwd_dkdv"): 866955260,
-    ("mid", "bwd_dq"): 859480756,
+    ("mid", "fwd"): 539392619,
+    ("mid", "delta"): 270641869,
+    ("mid", "bwd_dkdv"): 835155418,
+    ("mid", "bwd_dq"): 858409538,
 }
 
 

@@ -48,8 +48,12 @@ DEVI long pack_e4m3(const float (&v)[8]) {
 //               maximum, no accumulator rescale), LSE[] then receives m + log l as usual.
 constexpr int kRowStats = 3, kFixedNorm = 2;
 
+// Waves per SIMD are stated as a range, not only as a minimum: at D = 128 two work-groups fit a
+// CU (LDS), and told so the compiler spends the registers of the third wave it would otherwise
+// keep room for on issuing LDS fragment reads ahead of their matrix instructions.
 template <int D, bool CAUSAL, int VARIANT, bool RAGGED, bool EXTRAS>
-__global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_fwd_kernel(
+__global__ __launch_bounds__(256)
+__attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, D == 128 ? 2 : (D > 128 ? 1 : 8)))) void attn_fwd_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, float* __restrict__ LSE, int N, float alpha, float beta, float eps,
     FwdExtras ex, Layout lay) {
