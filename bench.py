@@ -169,6 +169,14 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom))},
     }
 
+    # secondary bound: one exponential per visible score in each of the three kernels (v_exp_f32
+    # issues at a quarter of the vector rate: 4 lanes per SIMD and clock)
+    exps = B * H * N * N * (0.5 if w.causal else 1.0)
+    exp_peak = 256 * 4 * 4 * 2.4e9
+    out["exp_rate"] = {"exps_per_kernel": exps, "peak_Texp/s": round(exp_peak / 1e12, 2),
+                       "achieved_Texp/s": {k: round(exps / (per[k] * 1e-3) / 1e12, 3) for k in per},
+                       "frac": {k: round(exps / (per[k] * 1e-3) / exp_peak, 4) for k in per}}
+
     # delta pass with cold caches: a 1 GiB fill in front of every timed launch evicts O and dO
     # from L2 and the 256 MB Infinity Cache (the figure above is a warm one: the forward has just
     # written O)

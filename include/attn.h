@@ -18,7 +18,7 @@
  *     LSE and delta are float32 [B][H][N].  Pointers must be 16-byte aligned.  Outputs must not
  *     alias inputs.
  *   - Self-attention: N queries and N keys.  causal != 0: query r attends to keys c <= r.
- *   - Supported shapes: d in {32, 64, 128, 256}; any N >= 1 (N need not be a multiple of a tile: the
+ *   - Supported shapes: d in {32, 64, 96, 128, 256}; any N >= 1 (N need not be a multiple of a tile: the
  *     kernels clamp their reads to row N-1 and store nothing past it); B*H*N*d < 2^40.
  *     B == 0 or H == 0 is a no-op that returns ATTN_OK.  Anything else: ATTN_ERR_UNSUPPORTED.
  *   - Return value: an attn_status.  No exceptions, aborts or global mutable state.

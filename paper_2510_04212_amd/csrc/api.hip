@@ -57,7 +57,7 @@ int check_shape(int B, int H, int N, int d, bool* empty) {
   *empty = false;
   if (B < 0 || H < 0 || N < 0 || d < 0) return ATTN_ERR_BAD_ARG;
   if (B == 0 || H == 0) { *empty = true; return ATTN_OK; }
-  if (d != 32 && d != 64 && d != 128 && d != 256) return ATTN_ERR_UNSUPPORTED;
+  if (d != 32 && d != 64 && d != 96 && d != 128 && d != 256) return ATTN_ERR_UNSUPPORTED;
   if (N == 0) return ATTN_ERR_UNSUPPORTED;
   const double elems = (double)B * H * (double)N * d;
   if (elems >= 1099511627776.0) return ATTN_ERR_UNSUPPORTED;      // 2^40
@@ -72,7 +72,7 @@ extern "C" const char* attn_status_string(int status) {
     case ATTN_OK: return "ATTN_OK";
     case ATTN_ERR_NULL: return "ATTN_ERR_NULL: a required pointer is NULL";
     case ATTN_ERR_BAD_ARG: return "ATTN_ERR_BAD_ARG: invalid argument value or misaligned pointer";
-    case ATTN_ERR_UNSUPPORTED: return "ATTN_ERR_UNSUPPORTED: d must be 32, 64, 128 or 256 and N positive";
+    case ATTN_ERR_UNSUPPORTED: return "ATTN_ERR_UNSUPPORTED: d must be 32, 64, 96, 128 or 256 and N positive";
     case ATTN_ERR_WORKSPACE: return "ATTN_ERR_WORKSPACE: workspace too small or misaligned";
     case ATTN_ERR_LAUNCH: return "ATTN_ERR_LAUNCH: HIP launch failed";
     default: return "unknown attn_status";

@@ -57,7 +57,7 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, int N, float alpha, Layout lay) {
-  constexpr int TILE_BYTES = kQTile * D * 2;
+  constexpr int TILE_BYTES = kQTile * kLdsD<D> * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   // layout: Q buffers [2][TILE_BYTES], dO buffers [2][TILE_BYTES], L2 [2][64] float, delta [2][64] float
   char* ldsQ = smem;
@@ -343,7 +343,7 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
           __builtin_amdgcn_sched_barrier(0);
         }
       };
-      if (DS == 1 && (!CAUSAL || qt0 + shift >= kw + 31) && (!RAGGED || qt0 + kQTile <= N)) {
+      if (DS == 1 && D != 96 && (!CAUSAL || qt0 + shift >= kw + 31) && (!RAGGED || qt0 + kQTile <= N)) {
         tile_pipelined();
       } else {
 #pragma unroll
@@ -402,7 +402,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ O, bf16_t* __restrict__ dQ, float* __restrict__ delta_out, int N,
     float alpha, Layout lay) {
   constexpr bool DELTA_MODE = MODE == kRecomputeDelta;
-  constexpr int TILE_BYTES = kKTile * D * 2;
+  constexpr int TILE_BYTES = kKTile * kLdsD<D> * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* ldsK = smem;
   char* ldsV = smem + 2 * TILE_BYTES;
@@ -442,7 +442,10 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
     // this lane holds chunks 2kc + h of its row: the chains of its chunks, the tree levels that
     // stay inside one parity class, and the last level (chunk 0 + chunk 1 classes) across the
     // two lanes of the row
-    float cs[D / 16];
+    constexpr int NCS = kLdsD<D> / 16;     // D = 96: the tree of a 128-wide row whose last chunks are zero
+    float cs[NCS];
+#pragma unroll
+    for (int kc = 0; kc < NCS; ++kc) cs[kc] = 0.f;
 #pragma unroll
     for (int kc = 0; kc < D / 16; ++kc) {
       const bf16x8 o8 = *reinterpret_cast<const bf16x8*>(O + head_off + (size_t)qc * sn + 16 * kc + 8 * h);
@@ -452,7 +455,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
       cs[kc] = c;
     }
 #pragma unroll
-    for (int off = D / 32; off >= 1; off >>= 1)
+    for (int off = NCS / 2; off >= 1; off >>= 1)
 #pragma unroll
       for (int kc = 0; kc < off; ++kc) cs[kc] += cs[kc + off];
     dl = sum_with_partner32(cs[0]);
@@ -572,7 +575,7 @@ template <int D, bool CAUSAL, bool RAGGED, bool GROUPED>
 static hipError_t launch_dkdv(const void* Q, const void* K, const void* V, const void* dO,
                               const float* LSE, const float* delta, void* dK, void* dV, int BH,
                               int N, float alpha, Layout lay, hipStream_t st) {
-  constexpr int smem = 4 * kQTile * D * 2 + 4 * kQTile * (int)sizeof(float);
+  constexpr int smem = 4 * kQTile * kLdsD<D> * 2 + 4 * kQTile * (int)sizeof(float);
   static bool set = false;
   auto k = attn_bwd_dkdv_kernel<D, CAUSAL, RAGGED, GROUPED>;
   hipError_t e;
@@ -588,7 +591,7 @@ template <int D, bool CAUSAL, bool RAGGED, int MODE>
 static hipError_t launch_dq(const void* Q, const void* K, const void* V, const void* dO,
                             const float* LSE, const float* delta, const void* O, void* dQ,
                             float* delta_out, int BH, int N, float alpha, Layout lay, hipStream_t st) {
-  constexpr int smem = 4 * kKTile * D * 2;
+  constexpr int smem = 4 * kKTile * kLdsD<D> * 2;
   static bool set = false;
   auto k = attn_bwd_dq_kernel<D, CAUSAL, RAGGED, MODE>;
   hipError_t e;
@@ -611,7 +614,7 @@ hipError_t attn_bwd_dkdv_dispatch(const void* Q, const void* K, const void* V, c
   if (d == DD && (causal != 0) == CC)                 \
     return launch_dkdv<DD, CC, true, true>(Q, K, V, dO, LSE, delta, dK, dV, BH, N, alpha, lay, st);
     CASEG(32, false) CASEG(32, true) CASEG(64, false) CASEG(64, true) CASEG(128, false) CASEG(128, true)
-    CASEG(256, false) CASEG(256, true)
+    CASEG(256, false) CASEG(256, true) CASEG(96, false) CASEG(96, true)
 #undef CASEG
     return hipErrorInvalidValue;
   }
@@ -622,6 +625,7 @@ hipError_t attn_bwd_dkdv_dispatch(const void* Q, const void* K, const void* V, c
   CASE(64, false, false) CASE(64, false, true) CASE(64, true, false) CASE(64, true, true)
   CASE(128, false, false) CASE(128, false, true) CASE(128, true, false) CASE(128, true, true)
   CASE(256, false, false) CASE(256, false, true) CASE(256, true, false) CASE(256, true, true)
+  CASE(96, false, false) CASE(96, false, true) CASE(96, true, false) CASE(96, true, true)
 #undef CASE
   return hipErrorInvalidValue;
 }
@@ -642,6 +646,7 @@ hipError_t attn_bwd_dq_dispatch(const void* Q, const void* K, const void* V, con
   CASE(64, false, false) CASE(64, false, true) CASE(64, true, false) CASE(64, true, true)
   CASE(128, false, false) CASE(128, false, true) CASE(128, true, false) CASE(128, true, true)
   CASE(256, false, false) CASE(256, false, true) CASE(256, true, false) CASE(256, true, true)
+  CASE(96, false, false) CASE(96, false, true) CASE(96, true, false) CASE(96, true, true)
 #undef CASE
   return hipErrorInvalidValue;
 }
@@ -655,7 +660,7 @@ hipError_t attn_delta_recompute_dispatch(const void* Q, const void* K, const voi
   if (d == DD && (causal != 0) == CC)                 \
     return launch_dq<DD, CC, true, kRecomputeDelta>(Q, K, V, dO, LSE, nullptr, nullptr, nullptr, delta_out, BH, N, alpha, lay, st);
   CASE(32, false) CASE(32, true) CASE(64, false) CASE(64, true) CASE(128, false) CASE(128, true)
-  CASE(256, false) CASE(256, true)
+  CASE(256, false) CASE(256, true) CASE(96, false) CASE(96, true)
 #undef CASE
   return hipErrorInvalidValue;
 }

@@ -30,6 +30,10 @@ DEVI f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// Width of an LDS tile row, in elements, for head size D.  The swizzle and the tile loader work on
+// power-of-two rows; D = 96 uses 128-wide rows of which the last 32 columns are never read.
+template <int D> constexpr int kLdsD = (D == 96) ? 128 : D;
+
 // Swizzle of the 16-byte chunk index inside one tile row, chosen so that (a) 16 lanes reading
 // the same chunk of 16 consecutive rows and (b) a transposing read touching 8 consecutive rows
 // x 64 bytes both spread over all 64 LDS banks.
@@ -49,8 +53,9 @@ template <> DEVI int swz<64>(int row) {
 // Byte offset of element (row, col) of a [rows][D] bf16 tile in LDS; col must be a multiple of 4
 // for 8-byte accesses and of 8 for 16-byte accesses.
 template <int D> DEVI int tile_off(int row, int col) {
+  constexpr int DL = kLdsD<D>;
   int chunk = col >> 3;
-  return row * (D * 2) + ((chunk ^ swz<D>(row)) << 4) + ((col & 7) << 1);
+  return row * (DL * 2) + ((chunk ^ swz<DL>(row)) << 4) + ((col & 7) << 1);
 }
 
 // 16-byte natural read: 8 consecutive columns of one row (an A/B fragment whose contraction
@@ -103,14 +108,14 @@ template <int D> DEVI void init_frag_offsets(FragOffsets<D>& fo, int lane) {
 }
 // rows row_base + (lane & 31), row_base a multiple of 16
 template <int D> DEVI bf16x8 lds_row8(const char* tile, const FragOffsets<D>& fo, int row_base, int kc) {
-  return *reinterpret_cast<const bf16x8*>(tile + fo.row[kc] + row_base * (D * 2));
+  return *reinterpret_cast<const bf16x8*>(tile + fo.row[kc] + row_base * (kLdsD<D> * 2));
 }
 // k-slots = rows row_base + 8*(j/4) + 4h + (j%4), column 32db + (lane & 31); row_base a multiple of 16
 template <int D> DEVI bf16x8 lds_col8(const char* tile, const FragOffsets<D>& fo, int row_base, int db) {
   typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
   union { struct { s16x4 lo, hi; } p; bf16x8 v; } u;
-  u.p.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + fo.col[0][db] + row_base * (D * 2)));
-  u.p.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + fo.col[1][db] + row_base * (D * 2)));
+  u.p.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + fo.col[0][db] + row_base * (kLdsD<D> * 2)));
+  u.p.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + fo.col[1][db] + row_base * (kLdsD<D> * 2)));
   return u.v;
 }
 
@@ -182,7 +187,14 @@ DEVI const bf16_t* wave_uniform(const bf16_t* p) {
 }
 
 template <int D> struct TileLoader {
-  static constexpr int CH = D / 8;               // 16-byte chunks per row
+  static constexpr int DL = kLdsD<D>;            // LDS row width
+  static constexpr int CH = DL / 8;              // 16-byte chunk slots per LDS row
+  // source chunk that lands in slot `slot` of LDS row `row`; slots whose chunk lies beyond the D
+  // columns (D < DL) re-fetch one of the row's real chunks, which nobody reads
+  static DEVI int src_chunk(int slot, int row) {
+    const int c = slot ^ swz<DL>(row);
+    return (D < DL && c >= D / 8) ? (c & 7) : c;
+  }
   static constexpr int RPI = 64 / CH;            // rows per wave-instruction
   static constexpr int NI = 64 / RPI / 4;        // instructions per wave (4 waves share a tile)
   unsigned voff[NI];                             // per-lane byte offset inside the source tile
@@ -194,10 +206,10 @@ template <int D> struct TileLoader {
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       const int row = (wave * NI + i) * RPI + lane / CH;
-      const int c = (lane % CH) ^ swz<D>(row);
+      const int c = src_chunk(lane % CH, row);
       voff[i] = (unsigned)(row * sn + c * 8) * 2u;
     }
-    lds_wave = (unsigned)(wave * NI * RPI * D * 2);
+    lds_wave = (unsigned)(wave * NI * RPI * DL * 2);
   }
   // Same for a source tile of which only the first `valid` rows (1..64) exist: rows beyond them
   // re-read the last valid row, so that nothing is fetched out of bounds and the LDS tile holds
@@ -209,12 +221,12 @@ template <int D> struct TileLoader {
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       const int row = (wave * NI + i) * RPI + lane / CH;
-      const int c = (lane % CH) ^ swz<D>(row);
+      const int c = src_chunk(lane % CH, row);
       const int rc = row < valid ? row : valid - 1;
       const unsigned vo = (unsigned)(rc * sn + c * 8) * 2u;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                    :
-                   : "s"(base + (unsigned)(i * RPI * D * 2)), "v"(vo), "s"(src)
+                   : "s"(base + (unsigned)(i * RPI * DL * 2)), "v"(vo), "s"(src)
                    : "m0");
     }
   }
@@ -234,7 +246,7 @@ template <int D> struct TileLoader {
     for (int i = 0; i < NI; ++i) {
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                    :
-                   : "s"(base + (unsigned)(i * RPI * D * 2)), "v"(voff[i]), "s"(src)
+                   : "s"(base + (unsigned)(i * RPI * DL * 2)), "v"(voff[i]), "s"(src)
                    : "m0");
     }
   }

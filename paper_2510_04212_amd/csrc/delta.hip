@@ -15,7 +15,7 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const void* __restrict_
                                                          int N, Layout lay) {
   const bf16_t* O = static_cast<const bf16_t*>(Ov);
   const float* Of = static_cast<const float*>(Ov);
-  constexpr int LPR = D / 8;             // lanes per row
+  constexpr int LPR = kLdsD<D> / 8;      // lanes per row (a power of two; D = 96: lanes 12..15 of a row idle)
   constexpr int RPB = 256 / LPR;         // rows per block per step
   const int sub = threadIdx.x % LPR;
   const int rib = threadIdx.x / LPR;
@@ -25,7 +25,7 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const void* __restrict_
 #pragma unroll
   for (int u = 0; u < UNROLL; ++u) {
     long rr = row + (long)u * RPB;
-    if (rr < rows) {
+    if (rr < rows && sub < D / 8) {
       // row rr of the [B,H,N] order -> its place in the (possibly strided) bf16 tensors
       const size_t at = head_base(lay, (int)(rr / N)) + (size_t)(rr % N) * lay.sn + sub * 8;
       if (OHP) {
@@ -72,14 +72,15 @@ hipError_t attn_delta_dispatch(const void* O, const void* dO, float* delta, long
                                int o_is_f32, Layout lay, hipStream_t st) {
   constexpr int UNROLL = 4;
   if (rows == 0) return hipSuccess;
-  if (d != 32 && d != 64 && d != 128 && d != 256) return hipErrorInvalidValue;
-  const int rpb = 256 / (d / 8) * UNROLL;
+  if (d != 32 && d != 64 && d != 96 && d != 128 && d != 256) return hipErrorInvalidValue;
+  const int rpb = 256 / ((d == 96 ? 128 : d) / 8) * UNROLL;
   dim3 grid((unsigned)((rows + rpb - 1) / rpb));
 #define LAUNCH(DD, HP)                                                                          \
   hipLaunchKernelGGL((attn_delta_kernel<DD, UNROLL, HP>), grid, dim3(256), 0, st, O,           \
                      (const bf16_t*)dO, delta, rows, N, lay)
   if (d == 256) { if (o_is_f32) LAUNCH(256, true); else LAUNCH(256, false); }
   else if (d == 128) { if (o_is_f32) LAUNCH(128, true); else LAUNCH(128, false); }
+  else if (d == 96) { if (o_is_f32) LAUNCH(96, true); else LAUNCH(96, false); }
   else if (d == 64) { if (o_is_f32) LAUNCH(64, true); else LAUNCH(64, false); }
   else              { if (o_is_f32) LAUNCH(32, true); else LAUNCH(32, false); }
 #undef LAUNCH

@@ -57,7 +57,7 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, D == 128 ? 2 : (D > 128 ? 1
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, float* __restrict__ LSE, int N, float alpha, float beta, float eps,
     FwdExtras ex, Layout lay) {
-  constexpr int TILE_BYTES = kBc * D * 2;
+  constexpr int TILE_BYTES = kBc * kLdsD<D> * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   // layout: K buffers [2][TILE_BYTES], then V buffers [2][TILE_BYTES]
 
@@ -366,13 +366,13 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, D == 128 ? 2 : (D > 128 ? 1
 
 }  // namespace
 
-extern "C" int attn_fwd_key_tile(int d) { return (d == 32 || d == 64 || d == 128 || d == 256) ? kBc : 0; }
+extern "C" int attn_fwd_key_tile(int d) { return (d == 32 || d == 64 || d == 96 || d == 128 || d == 256) ? kBc : 0; }
 
 template <int D, bool CAUSAL, int VARIANT, bool RAGGED, bool EXTRAS>
 static hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
                              int BH, int N, float alpha, float beta, float eps, FwdExtras ex,
                              Layout lay, hipStream_t st) {
-  constexpr int smem = 4 * kBc * D * 2;
+  constexpr int smem = 4 * kBc * kLdsD<D> * 2;
   static bool attr_set = false;
   auto kern = attn_fwd_kernel<D, CAUSAL, VARIANT, RAGGED, EXTRAS>;
   if (!attr_set) {
@@ -405,7 +405,7 @@ hipError_t attn_fwd_dispatch(const void* Q, const void* K, const void* V, void* 
     return launch_fwd<DD, CC, kFixedNorm, true, true>(Q, K, V, O, LSE, BH, N, alpha, beta, eps, ex, lay, st); \
   }
     CASE2(32, false) CASE2(32, true) CASE2(64, false) CASE2(64, true) CASE2(128, false) CASE2(128, true)
-    CASE2(256, false) CASE2(256, true)
+    CASE2(256, false) CASE2(256, true) CASE2(96, false) CASE2(96, true)
 #undef CASE2
     return hipErrorInvalidValue;
   }
@@ -419,6 +419,7 @@ hipError_t attn_fwd_dispatch(const void* Q, const void* K, const void* V, void* 
   CASE(64, false, 0) CASE(64, false, 1) CASE(64, true, 0) CASE(64, true, 1)
   CASE(128, false, 0) CASE(128, false, 1) CASE(128, true, 0) CASE(128, true, 1)
   CASE(256, false, 0) CASE(256, false, 1) CASE(256, true, 0) CASE(256, true, 1)
+  CASE(96, false, 0) CASE(96, false, 1) CASE(96, true, 0) CASE(96, true, 1)
 #undef CASE
   return hipErrorInvalidValue;
 }

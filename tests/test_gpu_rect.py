@@ -32,7 +32,7 @@ SHAPES = [(128, 256), (256, 128), (100, 333), (333, 100), (64, 1024), (1024, 64)
 
 
 @pytest.mark.parametrize("Nq,Nk", SHAPES)
-@pytest.mark.parametrize("d", [32, 64, 128, 256])
+@pytest.mark.parametrize("d", [32, 64, 96, 128, 256])
 @pytest.mark.parametrize("causal", [False, True])
 def test_rectangular_against_the_oracle(lib, Nq, Nk, d, causal):
     x = _inputs(Nq * 7 + Nk, 1, 2, Nq, Nk, d, scale=1.25)

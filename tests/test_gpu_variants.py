@@ -266,7 +266,7 @@ def test_whole_row_detection_sees_ties_that_straddle_tiles(lib):
         assert metrics.max_abs(_np(got["O"][0, 0]), O64) <= TOL_ABS
 
 
-@pytest.mark.parametrize("d,causal,N", [(64, True, 384), (128, True, 256), (128, False, 200), (64, False, 129), (32, True, 200), (256, True, 200)])
+@pytest.mark.parametrize("d,causal,N", [(64, True, 384), (128, True, 256), (128, False, 200), (64, False, 129), (32, True, 200), (256, True, 200), (96, True, 200)])
 def test_strided_layouts_give_bit_identical_results(lib, d, causal, N):
     """attn_fwd_strided / attn_bwd_strided on (a) a [B,N,H,d] buffer and (b) views into one fused
     [B,N,3,H,d] projection buffer, against the contiguous [B,H,N,d] entry points on the same
@@ -364,7 +364,7 @@ def test_autograd_wrapper(lib):
 
 
 @pytest.mark.parametrize("H,Hkv,N,d,causal", [(4, 4, 256, 64, True), (6, 2, 320, 64, True), (4, 1, 200, 128, True),
-                                              (8, 2, 256, 128, False), (3, 1, 65, 64, False), (4, 2, 192, 32, True), (4, 2, 200, 256, True)])
+                                              (8, 2, 256, 128, False), (3, 1, 65, 64, False), (4, 2, 192, 32, True), (4, 2, 200, 256, True), (6, 2, 200, 96, True)])
 def test_grouped_query_attention(lib, H, Hkv, N, d, causal):
     """attn_fwd_gqa / attn_bwd_gqa: O and dQ equal, bit for bit, ordinary attention on K, V repeated
     for every query head of a group; dK, dV (summed over the group in float32, rounded once)
@@ -415,7 +415,7 @@ def test_matrix_clock_probe(lib):
     assert raw.attn_probe_matrix_clock(None, 8, 10, None) == 1
 
 
-@pytest.mark.parametrize("B,H,N,d,causal", [(1, 2, 128, 64, True), (2, 2, 384, 128, True), (1, 3, 200, 64, False), (2, 2, 300, 32, True), (1, 2, 320, 256, True),
+@pytest.mark.parametrize("B,H,N,d,causal", [(1, 2, 128, 64, True), (2, 2, 384, 128, True), (1, 3, 200, 64, False), (2, 2, 300, 32, True), (1, 2, 320, 256, True), (2, 2, 300, 96, True),
                                              (1, 2, 333, 128, True), (1, 1, 1, 64, True), (1, 2, 1024, 128, False)])
 def test_dq_stage_forming_its_own_delta_gives_the_same_bits(lib, B, H, N, d, causal):
     """attn_bwd_dq_delta == attn_delta followed by attn_bwd_dq, bit for bit (delta and dQ), and

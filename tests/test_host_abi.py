@@ -39,11 +39,11 @@ def test_status_strings(binding):
 
 def test_key_tile_and_workspace_queries(binding):
     assert binding.fwd_key_tile(64) == 64 and binding.fwd_key_tile(128) == 64
-    assert binding.fwd_key_tile(96) == 0
+    assert binding.fwd_key_tile(96) == 64 and binding.fwd_key_tile(80) == 0
     assert binding.bwd_workspace_bytes(4, 32, 4096, 128) == 4 * 32 * 4096 * 4
     assert binding.bwd_workspace_bytes(1, 1, 128, 64) == 512          # rounded up to 256
     assert binding.bwd_workspace_bytes(1, 1, 100, 64) == 512          # any N >= 1 is accepted
-    assert binding.bwd_workspace_bytes(1, 1, 128, 96) == 0            # unsupported head dim
+    assert binding.bwd_workspace_bytes(1, 1, 128, 80) == 0            # unsupported head dim
     assert binding.bwd_workspace_bytes(0, 4, 128, 64) == 0
 
 
@@ -54,7 +54,7 @@ def test_argument_validation_happens_on_the_host(binding):
     p = ctypes.c_void_p(0x1000)          # a non-NULL, aligned fake pointer: never dereferenced
     mis = ctypes.c_void_p(0x1004)
     fwd = lambda Q, K, V, O, L, B, H, N, d, var=0, scale=0.125: lib.attn_fwd(Q, K, V, O, L, B, H, N, d, 1, scale, var, None)
-    assert fwd(p, p, p, p, p, 1, 1, 128, 96) == UNSUP        # head dim
+    assert fwd(p, p, p, p, p, 1, 1, 128, 80) == UNSUP        # head dim
     assert fwd(p, p, p, p, p, 1, 1, 0, 64) == UNSUP
     assert fwd(p, p, p, p, p, -1, 1, 128, 64) == BAD
     assert fwd(p, p, p, p, p, 1, 1, 128, 64, var=3) == BAD and fwd(p, p, p, p, p, 1, 1, 128, 64, var=-1) == BAD
@@ -75,20 +75,20 @@ def test_argument_validation_happens_on_the_host(binding):
     assert opt(q, None, None) == BAD                             # O_hp aliases O
     r_ = ctypes.c_void_p(0x3000)
     assert opt(None, r_, r_) == BAD                              # the two count outputs alias
-    assert lib.attn_fwd_opt(p, p, p, q, p, None, None, None, 1, 1, 128, 96, 1, 0.125, 0, 2.0, 1e-3, 0, None) == UNSUP
+    assert lib.attn_fwd_opt(p, p, p, q, p, None, None, None, 1, 1, 128, 80, 1, 0.125, 0, 2.0, 1e-3, 0, None) == UNSUP
     assert lib.attn_delta_hp(None, p, q, 1, 1, 128, 64, None) == NULL
     assert lib.attn_delta_hp(p, p, p, 1, 1, 128, 64, None) == BAD  # delta aliases an input
     assert lib.attn_delta_hp(None, None, None, 0, 3, 128, 64, None) == OK
     fs = lambda sb, sh, sn, d=64: lib.attn_fwd_strided(p, p, p, q, p, sb, sh, sn, 1, 1, 128, d, 1, 0.125, 0, 2.0, 1e-3, None)
     assert fs(0, 64, 64) == BAD and fs(8192, 8192, 60) == BAD and fs(8192, 8192, 32) == BAD   # zero, not a multiple of 8, rows overlap
-    assert fs(8192, 8192, 1 << 24) == BAD and fs(8192, 8192, 96, d=96) == UNSUP
+    assert fs(8192, 8192, 1 << 24) == BAD and fs(8192, 8192, 80, d=80) == UNSUP
     assert lib.attn_bwd_strided(*ptrs_for_strided, ws_for_strided, 4096, 8192, 8192, 4, 1, 1, 128, 64, 1, 0.125, 0, None) == BAD
     gq = lambda H, Hkv: lib.attn_fwd_gqa(p, p, p, q, p, 1, H, Hkv, 128, 64, 1, 0.125, 0, 2.0, 1e-3, None)
     assert gq(6, 4) == BAD and gq(4, 0) == BAD and gq(2, 4) == BAD and gq(0, 0) == OK
     assert lib.attn_bwd_gqa(*ptrs_for_strided, ws_for_strided, 4096, 1, 6, 4, 128, 64, 1, 0.125, 0, None) == BAD
     fr = lambda Nq, Nk, d=64, Q=p: lib.attn_fwd_rect(Q, p, p, q, p, 1, 1, Nq, Nk, d, 1, 0.125, 0, 2.0, 1e-3, None)
     assert fr(128, 0) == UNSUP and fr(0, 128) == UNSUP and fr(-1, 128) == BAD and fr(128, -1) == BAD
-    assert fr(128, 256, d=96) == UNSUP and fr(128, 256, Q=None) == NULL
+    assert fr(128, 256, d=80) == UNSUP and fr(128, 256, Q=None) == NULL
     assert lib.attn_fwd_rect(None, None, None, None, None, 0, 4, 128, 256, 64, 1, 0.125, 0, 2.0, 1e-3, None) == OK
     br = lambda Nq, Nk, wb: lib.attn_bwd_rect(*ptrs_for_strided, ws_for_strided, wb, 1, 1, Nq, Nk, 64, 1, 0.125, 0, None)
     assert br(128, 0, 4096) == UNSUP and br(200, 64, 512) == WS     # delta has Nq = 200 floats: 1024 bytes
