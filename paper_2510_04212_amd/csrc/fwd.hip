@@ -178,36 +178,45 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, D == 128 ? 2 : (D > 128 ? 1
           mneg = (RAGGED && m == -INFINITY) ? 0.f : -m * kLog2e;   // a query that sees no key at all
         } else {
           // ---- tile row maximum r_m (of the alpha-scaled scores)
-          float mx = s[0][0];
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
-          mx = max_with_partner32(mx);
-          const float r_m = mx * alpha;
-          float m_prime = r_m;
+          float mx;
+          bool repeated = false;
           if (VARIANT == 1) {
             // Alg. 3: r_s = #{ r_m - S <= eps } over the tile row; a repeated maximum moves the
-            // normaliser to beta*r_m (r_m > 0) or to 0 (r_m < 0).
-            // The count only matters through "more than one".  Each comparison yields a 64-lane
-            // mask in scalar registers; "seen once" / "seen twice" masks are then maintained with
-            // scalar instructions (one vector instruction per element instead of three), and the
-            // two lanes that share a query row are merged at the end.
-            const float thr = (r_m - eps) * inv_alpha;
-            unsigned long long once = 0ull, twice = 0ull;
+            // normaliser to beta*r_m (r_m > 0) or to 0 (r_m < 0).  The count only matters through
+            // "more than one", i.e. through whether the SECOND largest score of the row passes the
+            // test: the lane keeps the two largest of its 32 scores (two chains of 16; a value met
+            // twice is both), then the two lanes that share a query row are merged.  Two vector
+            // instructions per score and no mask bookkeeping.
+            float a1[2], a2[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+              a1[kb] = fmaxf(s[kb][0], s[kb][1]);
+              a2[kb] = fminf(s[kb][0], s[kb][1]);
+#pragma unroll
+              for (int i = 2; i < 16; ++i) {
+                a2[kb] = __builtin_amdgcn_fmed3f(a1[kb], a2[kb], s[kb][i]);
+                a1[kb] = fmaxf(a1[kb], s[kb][i]);
+              }
+            }
+            const float t1 = fmaxf(a1[0], a1[1]);
+            const float t2 = fmaxf(fminf(a1[0], a1[1]), fmaxf(a2[0], a2[1]));
+            const float o1 = partner32(t1), o2 = partner32(t2);
+            mx = fmaxf(t1, o1);
+            const float second = fmaxf(fminf(t1, o1), fmaxf(t2, o2));
+            // the test  r_m - alpha*s <= eps  in terms of the raw score:  s >= (r_m - eps) / alpha
+            // (a row with nothing visible in this tile has r_m = -inf: no rule, no update)
+            repeated = second >= (mx * alpha - eps) * inv_alpha && (!RAGGED || mx > -INFINITY);
+          } else {
+            mx = s[0][0];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-              for (int i = 0; i < 16; ++i) {
-                const unsigned long long hit = __builtin_amdgcn_ballot_w64(s[kb][i] >= thr);
-                twice |= once & hit;
-                once |= hit;
-              }
-            const unsigned long long once_sw = (once >> 32) | (once << 32);
-            const unsigned long long twice_sw = (twice >> 32) | (twice << 32);
-            const unsigned long long rep = twice | twice_sw | (once & once_sw);
-            // (a row with nothing visible in this tile has r_m = -inf: no rule, no update)
-            const bool repeated = ((rep >> lane) & 1ull) != 0ull && (!RAGGED || mx > -INFINITY);
+              for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
+            mx = max_with_partner32(mx);
+          }
+          const float r_m = mx * alpha;
+          float m_prime = r_m;
+          if (VARIANT == 1) {
             m_prime = (repeated && r_m > 0.f) ? beta * r_m : r_m;
             m_prime = (repeated && r_m < 0.f) ? 0.f : m_prime;
             if (EXTRAS) fired_cnt += (m_prime != r_m) ? 1 : 0;
