@@ -27,10 +27,10 @@ PEAK_HBM_GBS = 8000.0
 # scaled by the same counter's reading for a 1 GiB device copy (see profiles/mid_hbm_traffic.txt).
 # Keyed by (workload, kernel); None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("mid", "fwd"): 539392619,
-    ("mid", "delta"): 270641869,
-    ("mid", "bwd_dkdv"): 835155418,
-    ("mid", "bwd_dq"): 858409538,
+    ("mid", "fwd"): 539529654,
+    ("mid", "delta"): 270666765,
+    ("mid", "bwd_dkdv"): 819658229,
+    ("mid", "bwd_dq"): 861542968,
 }
 
 
@@ -246,6 +246,29 @@ def main():
                                "sample": f"fp64 numpy oracle (oracle.exact.forward_backward) on the first {heads_done} of "
                                          f"{B * H} heads of the same workload, {t_cpu:.1f} s; FLOPs counted by the same "
                                          f"causal-useful convention (the oracle itself forms the full N x N matrices)"}
+        # third part of the metric: mean signed error of O against the fp64 oracle on the
+        # repeated-maximum stress inputs, standard vs mitigated forward, on a sample of heads
+        # (same oracle leg: nothing outside this block touches oracle/)
+        from oracle import metrics
+        signed = {}
+        for name in ("pairs_skew", "tied"):
+            ws = synth.WORKLOADS[name]
+            xs_ = synth.make(ws, dev)
+            heads = [(b, h) for b in range(ws.B) for h in range(0, ws.H, 4)]
+            ref = {bh: exact.forward(*(xs_[k][bh[0], bh[1]].double().cpu().numpy() for k in ("Q", "K", "V")),
+                                     ws.alpha, ws.causal)[0] for bh in heads}
+            entry = {"heads": len(heads)}
+            for label, var in (("standard", binding.STANDARD), ("mitigated", binding.MITIGATED)):
+                Og, _ = binding.attn_fwd(xs_["Q"], xs_["K"], xs_["V"], ws.causal, ws.alpha, var)
+                got = np.concatenate([Og[b, h].double().cpu().numpy().ravel() for (b, h) in heads])
+                want = np.concatenate([ref[bh].ravel() for bh in heads])
+                entry[label] = {"mean_signed_error_O": float(metrics.mean_signed(got, want)),
+                                "noise": float(metrics.mean_signed_noise(got, want)),
+                                "max_abs": float(metrics.max_abs(got, want))}
+            entry["standard_over_mitigated"] = round(abs(entry["standard"]["mean_signed_error_O"]) /
+                                                     max(abs(entry["mitigated"]["mean_signed_error_O"]), 1e-30), 1)
+            signed[name] = entry
+        out["mean_signed_error_vs_fp64"] = signed
     print(json.dumps(out))
 
 
