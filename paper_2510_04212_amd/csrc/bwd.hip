@@ -21,6 +21,7 @@
 // multiplies the float32 dQ / dK accumulators once; outputs are rounded to bf16 when stored.
 #include "common.hpp"
 
+#include <atomic>
 #include <type_traits>
 
 namespace {
@@ -563,11 +564,11 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
 }
 
 template <typename KernT>
-static hipError_t set_smem(KernT kern, int smem, bool& done) {
-  if (done) return hipSuccess;
+static hipError_t set_smem(KernT kern, int smem, std::atomic<bool>& done) {
+  if (done.load(std::memory_order_acquire)) return hipSuccess;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-  if (e == hipSuccess) done = true;
+  if (e == hipSuccess) done.store(true, std::memory_order_release);
   return e;
 }
 
@@ -576,7 +577,7 @@ static hipError_t launch_dkdv(const void* Q, const void* K, const void* V, const
                               const float* LSE, const float* delta, void* dK, void* dV, int BH,
                               int N, float alpha, Layout lay, hipStream_t st) {
   constexpr int smem = 4 * kQTile * kLdsD<D> * 2 + 4 * kQTile * (int)sizeof(float);
-  static bool set = false;
+  static std::atomic<bool> set{false};
   auto k = attn_bwd_dkdv_kernel<D, CAUSAL, RAGGED, GROUPED>;
   hipError_t e;
   if ((e = set_smem(k, smem, set)) != hipSuccess) return e;
@@ -592,7 +593,7 @@ static hipError_t launch_dq(const void* Q, const void* K, const void* V, const v
                             const float* LSE, const float* delta, const void* O, void* dQ,
                             float* delta_out, int BH, int N, float alpha, Layout lay, hipStream_t st) {
   constexpr int smem = 4 * kKTile * kLdsD<D> * 2;
-  static bool set = false;
+  static std::atomic<bool> set{false};
   auto k = attn_bwd_dq_kernel<D, CAUSAL, RAGGED, MODE>;
   hipError_t e;
   if ((e = set_smem(k, smem, set)) != hipSuccess) return e;

@@ -11,6 +11,7 @@
 // which keeps the per-query rescale factor uniform over a lane's accumulator registers.
 #include "common.hpp"
 
+#include <atomic>
 #include <type_traits>
 
 namespace {
@@ -382,13 +383,13 @@ static hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* 
                              int BH, int N, float alpha, float beta, float eps, FwdExtras ex,
                              Layout lay, hipStream_t st) {
   constexpr int smem = 4 * kBc * kLdsD<D> * 2;
-  static bool attr_set = false;
+  static std::atomic<bool> attr_set{false};   // (calls from several host threads may race to set it: harmless, the call is idempotent)
   auto kern = attn_fwd_kernel<D, CAUSAL, VARIANT, RAGGED, EXTRAS>;
-  if (!attr_set) {
+  if (!attr_set.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set.store(true, std::memory_order_release);
   }
   dim3 grid(BH * ((N + kBr - 1) / kBr));
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, (const bf16_t*)Q, (const bf16_t*)K,
