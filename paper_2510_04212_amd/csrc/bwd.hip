@@ -107,6 +107,8 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
 #pragma unroll
       for (int db = 0; db < D / 32; ++db) fo_upd.col[half][db] ^= 64 * db0;
   }
+  frag_offsets_add_base<D>(fo, lds_address(smem));
+  frag_offsets_add_base<D>(fo_upd, lds_address(smem));
   TileLoader<D> loader;
   loader.init(tid, sn);
 
@@ -191,8 +193,8 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
           load_tile(Qh, dOh, Lh, Dh, t + 1, buf ^ 1);
         }
       }
-      const char* tQ = smem + buf * TILE_BYTES;
-      const char* tdO = smem + (2 + buf) * TILE_BYTES;
+      constexpr int tQ = buf * TILE_BYTES;          // byte offsets of this tile's Q and dO in smem
+      constexpr int tdO = (2 + buf) * TILE_BYTES;
       const float* tL = reinterpret_cast<const float*>(smem + 4 * TILE_BYTES) + buf * kQTile;
       const float* tD = reinterpret_cast<const float*>(smem + 4 * TILE_BYTES) + 2 * kQTile + buf * kQTile;
       const int qt0 = t * kQTile;

@@ -92,10 +92,20 @@ template <int D> DEVI bf16x8 lds_read_col8(const char* tile, int row_base, int c
 // constant to the byte offset: per lane, D/16 offsets serve every row-major (natural) fragment
 // and 2 x D/32 offsets every column-major (transposing) one; the rest folds into the
 // instruction's immediate offset when the tile address is a compile-time constant.
+// The offsets are made absolute LDS addresses once (frag_offsets_add_base); the fragment readers
+// below then address LDS as "per-lane register + compile-time constant", which the compiler
+// turns into the instruction's immediate offset.  (With the shared-memory symbol in the address
+// expression instead, it re-adds the symbol's address - a link-time value - in a vector
+// instruction in front of every read.)
 template <int D> struct FragOffsets {
   int row[D / 16];          // natural read of columns 16kc + 8h .. +7 of row (lane & 31)
   int col[2][D / 32];       // transposing reads: rows 4h + 8*half + 0..3, column 32db + (lane & 31)
 };
+// 32-bit LDS address of a pointer into shared memory
+DEVI int lds_address(const void* p) {
+  typedef __attribute__((address_space(3))) const char lds_char;
+  return (int)(unsigned)(unsigned long)((lds_char*)p);
+}
 template <int D> DEVI void init_frag_offsets(FragOffsets<D>& fo, int lane) {
   const int r = lane & 31, h = lane >> 5, i = lane & 15;
 #pragma unroll
@@ -106,16 +116,37 @@ template <int D> DEVI void init_frag_offsets(FragOffsets<D>& fo, int lane) {
     for (int db = 0; db < D / 32; ++db)
       fo.col[half][db] = tile_off<D>(4 * h + 8 * half + (i >> 2), 32 * db + (lane & 16) + ((i & 3) << 2));
 }
+// shared_base: LDS address of the array the tiles live in (lds_address(smem))
+// (each sum passes through an empty asm statement: otherwise the compiler, rather than keep it in
+// a register, re-adds the base in front of every use)
+template <int D> DEVI void frag_offsets_add_base(FragOffsets<D>& fo, int shared_base) {
+#pragma unroll
+  for (int kc = 0; kc < D / 16; ++kc) {
+    fo.row[kc] += shared_base;
+    asm volatile("" : "+v"(fo.row[kc]));
+  }
+#pragma unroll
+  for (int half = 0; half < 2; ++half)
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) {
+      fo.col[half][db] += shared_base;
+      asm volatile("" : "+v"(fo.col[half][db]));
+    }
+}
+// `tile`: byte offset of the tile inside the shared-memory array (fo holds absolute addresses).
 // rows row_base + (lane & 31), row_base a multiple of 16
-template <int D> DEVI bf16x8 lds_row8(const char* tile, const FragOffsets<D>& fo, int row_base, int kc) {
-  return *reinterpret_cast<const bf16x8*>(tile + fo.row[kc] + row_base * (kLdsD<D> * 2));
+template <int D> DEVI bf16x8 lds_row8(int tile, const FragOffsets<D>& fo, int row_base, int kc) {
+  typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8;
+  return *reinterpret_cast<lds_bf16x8*>((unsigned long)(unsigned)(fo.row[kc] + tile + row_base * (kLdsD<D> * 2)));
 }
 // k-slots = rows row_base + 8*(j/4) + 4h + (j%4), column 32db + (lane & 31); row_base a multiple of 16
-template <int D> DEVI bf16x8 lds_col8(const char* tile, const FragOffsets<D>& fo, int row_base, int db) {
+template <int D> DEVI bf16x8 lds_col8(int tile, const FragOffsets<D>& fo, int row_base, int db) {
   typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
   union { struct { s16x4 lo, hi; } p; bf16x8 v; } u;
-  u.p.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + fo.col[0][db] + row_base * (kLdsD<D> * 2)));
-  u.p.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + fo.col[1][db] + row_base * (kLdsD<D> * 2)));
+  u.p.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (lds_s16x4*)(unsigned long)(unsigned)(fo.col[0][db] + tile + row_base * (kLdsD<D> * 2)));
+  u.p.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (lds_s16x4*)(unsigned long)(unsigned)(fo.col[1][db] + tile + row_base * (kLdsD<D> * 2)));
   return u.v;
 }
 

@@ -54,7 +54,7 @@ constexpr int kRowStats = 3, kFixedNorm = 2;
 // keep room for on issuing LDS fragment reads ahead of their matrix instructions.
 template <int D, bool CAUSAL, int VARIANT, bool RAGGED, bool EXTRAS>
 __global__ __launch_bounds__(256)
-__attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, D == 128 ? 2 : (D > 128 ? 1 : 8)))) void attn_fwd_kernel(
+__attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 128 ? 1 : 8)))) void attn_fwd_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, float* __restrict__ LSE, int N, float alpha, float beta, float eps,
     FwdExtras ex, Layout lay) {
@@ -91,6 +91,7 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, D == 128 ? 2 : (D > 128 ? 1
   loader.init(tid, sn);
   FragOffsets<D> fo;
   init_frag_offsets<D>(fo, lane);
+  frag_offsets_add_base<D>(fo, lds_address(smem));
 
   // keys [0, kend) can matter to this block
   const int kend = !CAUSAL ? NK : !RAGGED ? q0 + kBr : max(0, min(NK, q0 + kBr + shift));
@@ -130,8 +131,8 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, D == 128 ? 2 : (D > 128 ? 1
   // address is a precomputed per-lane offset plus an immediate.
   auto tile_step = [&](auto buf_c, int j) {
     constexpr int BUF = decltype(buf_c)::value;
-    const char* tK = smem + BUF * TILE_BYTES;
-    const char* tV = smem + (2 + BUF) * TILE_BYTES;
+    constexpr int tK = BUF * TILE_BYTES;          // byte offsets of this tile's K and V in smem
+    constexpr int tV = (2 + BUF) * TILE_BYTES;
     if (j + 1 < ntiles) {   // lands in the other buffer while this tile is being processed
       loader.template load_rows<RAGGED>(smem + (BUF ^ 1) * TILE_BYTES, Kh, (j + 1) * kBc, NK, tid);
       if (VARIANT != kRowStats)
