@@ -217,14 +217,16 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
           dp = mfma32(lds_row8<D>(tdO, fo, 32 * qb, kc), vf[kc], dp);
         }
         sched_reads_ahead_of_mfma<D / 8, 1, 4>();
+        // element i of this lane is query qb0 + 4h + c with c = 8 (i / 4) + i % 4 a compile-time constant
         if (tail) {   // rows past the sequence end: P = exp(-inf) = 0, so they add nothing to dK, dV
+          const int lim = N - qb0 - 4 * h;
 #pragma unroll
           for (int i = 0; i < 16; ++i)
-            if (qb0 + 8 * (i >> 2) + 4 * h + (i & 3) >= N) s[i] = -INFINITY;
+            if (8 * (i >> 2) + (i & 3) >= lim) s[i] = -INFINITY;
         }
         // ---- P = exp(S - L) (step 9), dS = P o (dP - delta) (step 12)
         bf16x8 pf[2], dsf[2];
-        const int key = kw + r;
+        const int first_seen = kw + r - shift - qb0 - 4 * h;   // DIAG: queries with c below it do not see this lane's key
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const f32x4 l4 = *reinterpret_cast<const f32x4*>(tL + 32 * qb + 8 * g + 4 * h);
@@ -233,8 +235,7 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
             const int i = 4 * g + e;
             float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l4[e]));
             if (DIAG) {
-              int q = qb0 + 8 * g + 4 * h + e;
-              if (key > q + shift) p = 0.f;
+              if (8 * g + e < first_seen) p = 0.f;
             }
             float ds = p * dp[i];                     // dp already holds dP - delta
             pf[i >> 3][i & 7] = (bf16_t)p;
@@ -517,19 +518,20 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
           dp = mfma32(lds_read_row8<D>(tV, 32 * kb + r, 16 * kc + 8 * h), dof[kc], kc == 0 ? neg_delta : dp);
         }
         sched_reads_ahead_of_mfma<D / 8, 1, 4>();
+        // element i of this lane is key kb0 + 4h + c with c = 8 (i / 4) + i % 4 a compile-time constant
         if (tail) {   // keys past the sequence end: P = exp(-inf) = 0, so they add nothing to dQ
+          const int lim = NK - kb0 - 4 * h;
 #pragma unroll
           for (int i = 0; i < 16; ++i)
-            if (kb0 + 8 * (i >> 2) + 4 * h + (i & 3) >= NK) s[i] = -INFINITY;
+            if (8 * (i >> 2) + (i & 3) >= lim) s[i] = -INFINITY;
         }
         bf16x8 dsf[2];
-        const int q = qw + r;
+        const int last_seen = qw + r + shift - kb0 - 4 * h;   // DIAG: keys with c above it lie in this lane's future
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l2));
           if (DIAG) {
-            int key = kb0 + 8 * (i >> 2) + 4 * h + (i & 3);
-            if (key > q + shift) p = 0.f;
+            if (8 * (i >> 2) + (i & 3) > last_seen) p = 0.f;
           }
           if (DELTA_MODE) pdp = __builtin_fmaf(p, dp[i], pdp);
           else dsf[i >> 3][i & 7] = (bf16_t)(p * dp[i]);      // dp already holds dP - delta

@@ -156,13 +156,15 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
       // ---- mask: causal (key > query) in the tile that crosses the diagonal, and keys beyond
       // the sequence end in the last, partial tile -> -inf
       if ((CAUSAL && (k0 + kBc - 1 > qw + shift)) || (RAGGED && k0 + kBc > NK)) {
+        // element (kb, i) of this lane is key k0 + 4h + c with c = 32 kb + 8 (i / 4) + i % 4 a
+        // compile-time constant: masked <=> c > lim, one per-lane limit for both conditions
+        int lim = CAUSAL ? q + shift - k0 - 4 * h : 0x7fffffff;
+        if (RAGGED) lim = min(lim, NK - 1 - k0 - 4 * h);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            int key = k0 + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
-            if ((CAUSAL && key > q + shift) || (RAGGED && key >= NK)) s[kb][i] = -INFINITY;
-          }
+          for (int i = 0; i < 16; ++i)
+            if (32 * kb + 8 * (i >> 2) + (i & 3) > lim) s[kb][i] = -INFINITY;
       }
       if (VARIANT == kRowStats) {
         // two largest values seen by this lane (duplicates count: a value met twice is both)
