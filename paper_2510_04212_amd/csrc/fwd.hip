@@ -189,17 +189,21 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
             // normaliser to beta*r_m (r_m > 0) or to 0 (r_m < 0).  The count only matters through
             // "more than one", i.e. through whether the SECOND largest score of the row passes the
             // test: the lane keeps the two largest of its 32 scores (two chains of 16; a value met
-            // twice is both), then the two lanes that share a query row are merged.  Two vector
-            // instructions per score and no mask bookkeeping.
+            // twice is both), then the two lanes that share a query row are merged.  Three vector
+            // instructions per two scores and no mask bookkeeping.
             float a1[2], a2[2];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
               a1[kb] = fmaxf(s[kb][0], s[kb][1]);
               a2[kb] = fminf(s[kb][0], s[kb][1]);
 #pragma unroll
-              for (int i = 2; i < 16; ++i) {
-                a2[kb] = __builtin_amdgcn_fmed3f(a1[kb], a2[kb], s[kb][i]);
-                a1[kb] = fmaxf(a1[kb], s[kb][i]);
+              for (int i = 2; i < 16; i += 2) {
+                // two more scores x, y: the largest of {a1, x, y} is the new a1; the second largest
+                // of {a1, a2, x, y} is the median of {a1, x, y} or the old a2 (a2 <= a1)
+                const float x = s[kb][i], y = s[kb][i + 1];
+                const float mid = __builtin_amdgcn_fmed3f(a1[kb], x, y);
+                a1[kb] = fmaxf(fmaxf(a1[kb], x), y);
+                a2[kb] = fmaxf(mid, a2[kb]);
               }
             }
             const float t1 = fmaxf(a1[0], a1[1]);
