@@ -27,10 +27,10 @@ PEAK_HBM_GBS = 8000.0
 # scaled by the same counter's reading for a 1 GiB device copy (see profiles/mid_hbm_traffic.txt).
 # Keyed by (workload, kernel); None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("mid", "fwd"): 559832504,
-    ("mid", "delta"): 270667894,
-    ("mid", "bwd_dkdv"): 817702197,
-    ("mid", "bwd_dq"): 855728872,
+    ("mid", "fwd"): 557774911,
+    ("mid", "delta"): 270666298,
+    ("mid", "bwd_dkdv"): 821819545,
+    ("mid", "bwd_dq"): 859659636,
 }
 
 
