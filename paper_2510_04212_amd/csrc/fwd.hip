@@ -264,7 +264,7 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
               }
             }
           lsum = lsum * corr + psum8;
-          if (VARIANT != kFixedNorm && __builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {
+          if (VARIANT != kFixedNorm && j > 0 && __builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {
 #pragma unroll
             for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -302,8 +302,9 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
               if (EXTRAS) ones_cnt += ((float)pp[0] == 1.0f ? 1 : 0) + ((float)pp[1] == 1.0f ? 1 : 0);
             }
         lsum = lsum * corr + psum;
-        // ---- O^T <- diag(corr) O^T + V_j^T P-bar^T (Alg. 1 step 8)
-        if (VARIANT != kFixedNorm && __builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {
+        // ---- O^T <- diag(corr) O^T + V_j^T P-bar^T (Alg. 1 step 8); in the first tile the
+        // accumulator is still zero (corr = exp(-inf) = 0 there), nothing to rescale
+        if (VARIANT != kFixedNorm && j > 0 && __builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {
 #pragma unroll
           for (int db = 0; db < D / 32; ++db)
 #pragma unroll
