@@ -34,6 +34,30 @@ def test_extras_do_not_change_the_ordinary_outputs(lib, name, variant):
     assert torch.equal(O, r["O"]) and torch.equal(L, r["LSE"])
 
 
+@pytest.mark.parametrize("d", [32, 96, 128, 256])
+@pytest.mark.parametrize("variant", [0, 1, 2])
+def test_extras_at_every_head_size(lib, d, variant):
+    """The kernels with optional outputs and the whole-row variant at the head sizes the named
+    workloads do not have: ordinary outputs unchanged by the extras, O_hp within float32 rounding
+    of the exact O times the bf16 error bound, every row's unit-probability count at least 1 with
+    the standard normaliser, and the whole-row variant within tolerance of the fp64 oracle."""
+    B, H, N = 1, 2, 200
+    g = torch.Generator().manual_seed(77 + d + variant)
+    x = {k: torch.randn((B, H, N, d), generator=g).to(torch.bfloat16).to(DEV) for k in ("Q", "K", "V")}
+    alpha = d ** -0.5
+    O, L = lib.attn_fwd(x["Q"], x["K"], x["V"], True, alpha, variant)
+    r = lib.attn_fwd_opt(x["Q"], x["K"], x["V"], True, alpha, variant, want_O_hp=True, want_counts=True)
+    torch.cuda.synchronize()
+    assert torch.equal(O, r["O"]) and torch.equal(L, r["LSE"])
+    for h in range(H):
+        O64, L64 = exact.forward(_np(x["Q"][0, h]), _np(x["K"][0, h]), _np(x["V"][0, h]), alpha, True)
+        assert metrics.max_abs(_np(O[0, h]), O64) <= TOL_ABS
+        assert metrics.max_abs(_np(r["O_hp"][0, h]), O64) <= TOL_ABS
+        assert metrics.max_abs(_np(L[0, h]), L64) < 5e-3      # l sums bf16-rounded probabilities
+    if variant == 0:
+        assert int(r["ones"].min()) >= 1
+
+
 @pytest.mark.parametrize("name,heads", [("tiny", [(0, 0)]), ("gpt2s", [(0, 0), (7, 11)]), ("pairs_skew", [(1, 5)])])
 @pytest.mark.parametrize("variant", [0, 1])
 def test_high_precision_output_and_delta_hp(lib, name, heads, variant):
