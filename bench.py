@@ -206,6 +206,16 @@ def main():
                                 "note": "pure v_mfma_f32_32x32x16_bf16 loop, no memory traffic; nominal peak "
                                         f"{PEAK_BF16_TFLOPS:.0f} TFLOP/s assumes 2.4 GHz"}
 
+    # and what the LDS delivers: every matrix instruction of the three kernels takes one fresh
+    # 1 KB operand fragment from LDS, as one ds_read_b128 or as two transposing ds_read_b64_tr_b16
+    lds128 = binding.probe_lds_clock(kind=0, workgroups=256, iters=20000)
+    ldstr = binding.probe_lds_clock(kind=1, workgroups=256, iters=20000)
+    out["lds_probe"] = {"ds_read_b128_bytes_per_clk_per_cu": round(lds128["bytes_per_clk_per_cu"], 1),
+                        "ds_read_b64_tr_b16_bytes_per_clk_per_cu": round(ldstr["bytes_per_clk_per_cu"], 1),
+                        "note": "read-only loops, 4 waves per CU: one wave-wide LDS read instruction per 4 clocks and CU "
+                                "whatever its width; a matrix instruction (32 clocks per SIMD, 8 per CU) leaves room for "
+                                "two such reads"}
+
     # the other two throughput workloads of the build target, same step, fewer repetitions
     also = {}
     for name in ("gpt2s", "mid", "long", "long_full"):

@@ -36,7 +36,59 @@ __global__ __launch_bounds__(256, 2) void mfma_probe_kernel(long long* __restric
   if (blockIdx.x == 0 && threadIdx.x == 0) { out[0] = c1 - c0; out[1] = w1 - w0; }
 }
 
+// The same for the LDS: four waves per work-group, each issuing 16 * iters conflict-free LDS
+// reads from a 16 KB window and nothing else.  KIND 0: ds_read_b128 (64 lanes x 16 bytes = 1 KB
+// per instruction, one matrix-instruction operand fragment); KIND 1: ds_read_b64_tr_b16 (the
+// transposing read, 512 bytes per instruction, two per fragment).  Bytes read / elapsed shader
+// cycles is the LDS read bandwidth per CU the kernels' fragment traffic has to fit into.
+template <int KIND>
+__global__ __launch_bounds__(256, 1) void lds_probe_kernel(long long* __restrict__ out, int iters) {
+  __shared__ __attribute__((aligned(16))) char lds[16384];
+  for (int i = threadIdx.x; i < 4096; i += 256) reinterpret_cast<float*>(lds)[i] = (float)i;
+  __syncthreads();
+  const int lane = threadIdx.x & 63;
+  const long long c0 = clock64(), w0 = wall_clock64();
+  if (KIND == 0) {
+    const char* base = lds + lane * 16;
+    for (int it = 0; it < iters; ++it) {
+      u32x4 t[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) t[j] = *reinterpret_cast<const u32x4*>(base + j * 1024);
+      // all 16 bytes of every read are "used" by an empty asm statement: no vector instruction
+      // competes with the reads, and the compiler cannot narrow them
+#pragma unroll
+      for (int j = 0; j < 16; ++j) asm volatile("" : : "v"(t[j]));
+    }
+  } else {
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    // the access pattern of the kernels' transposing reads on a 128-column tile: 16 lanes cover
+    // 4 rows x 32 bytes, the four 16-lane groups of a wave four different 4-row bands
+    // (16 different addresses per pass: identical ones would be merged by the compiler)
+    const int i = lane & 15;
+    const char* base[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      base[c] = lds + tile_off<128>(4 * (lane >> 4) + (i >> 2), 32 * c + ((i & 3) << 2));
+    for (int it = 0; it < iters; ++it) {
+      s16x4 t[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        t[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(base[j >> 2] + (j & 3) * 4096));
+#pragma unroll
+      for (int j = 0; j < 16; ++j) asm volatile("" : : "v"(t[j]));
+    }
+  }
+  const long long c1 = clock64(), w1 = wall_clock64();
+  if (blockIdx.x == 0 && threadIdx.x == 0) { out[0] = c1 - c0; out[1] = w1 - w0; }
+}
+
 }  // namespace
+
+hipError_t attn_probe_lds_dispatch(long long* out, int kind, int workgroups, int iters, hipStream_t st) {
+  if (kind == 0) hipLaunchKernelGGL(lds_probe_kernel<0>, dim3(workgroups), dim3(256), 0, st, out, iters);
+  else hipLaunchKernelGGL(lds_probe_kernel<1>, dim3(workgroups), dim3(256), 0, st, out, iters);
+  return hipGetLastError();
+}
 
 hipError_t attn_probe_dispatch(long long* out, int workgroups, int iters, hipStream_t st) {
   hipLaunchKernelGGL(mfma_probe_kernel, dim3(workgroups), dim3(256), 0, st, out, iters);

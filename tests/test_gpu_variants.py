@@ -426,6 +426,21 @@ def test_grouped_query_attention(lib, H, Hkv, N, d, causal):
                 assert metrics.max_abs(got, ref) <= max(TOL_ABS, 2.0 ** -8 * np.abs(ref).max())
 
 
+def test_lds_probe(lib):
+    """The LDS read loops report the hardware's rates: one wave-wide read instruction per 4 clocks
+    and CU, i.e. 256 bytes per clock for ds_read_b128 and 128 for the transposing 8-byte read."""
+    r = lib.probe_lds_clock(kind=0, workgroups=256, iters=2000)
+    assert 200.0 < r["bytes_per_clk_per_cu"] <= 257.0, r
+    assert 1.0 < r["shader_clock_ghz"] < 2.6, r
+    t = lib.probe_lds_clock(kind=1, workgroups=256, iters=2000)
+    assert 100.0 < t["bytes_per_clk_per_cu"] <= 129.0, t
+    raw = lib.raw()
+    out = torch.zeros(4, dtype=torch.int64, device=DEV)
+    assert raw.attn_probe_lds_clock(out.data_ptr(), 0, 0, 10, None) == 2
+    assert raw.attn_probe_lds_clock(out.data_ptr(), 2, 8, 10, None) == 2
+    assert raw.attn_probe_lds_clock(None, 0, 8, 10, None) == 1
+
+
 def test_matrix_clock_probe(lib):
     """The benchmark's measurement aid: plausible clock and rate, argument checks."""
     p = lib.probe_matrix_clock(workgroups=512, iters=2000)
