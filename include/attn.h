@@ -80,8 +80,10 @@ int attn_fwd_key_tile(int d);
  * attn_fwd_ex additionally takes beta > 1 and eps >= 0 (both ignored by the standard variant).
  * eps and the sign tests of Alg. 3 apply to the alpha-scaled scores.
  * Note (Sec. 4, "larger values risk underflow"): when a repeated maximum satisfies
- * (beta-1)*r_m > ~87, every exp underflows, l = 0 and that row of O is NaN; this is the
- * algorithm's own limit and is not masked.
+ * (beta-1)*r_m > ~87.3, every exp underflows (the hardware exponential returns 0 below 2^-126),
+ * l = 0, that row of O is NaN and its LSE is -inf -- which is how a caller can detect it: with
+ * N queries and N keys no other row has LSE = -inf.  This is the algorithm's own limit and is
+ * not masked here; attn_fwd_opt has an opt-in guard (ATTN_FWD_GUARD_UNDERFLOW).
  */
 int attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
              int B, int H, int N, int d, int causal, float softmax_scale, int variant,
@@ -112,11 +114,21 @@ int attn_fwd_ex(const void* Q, const void* K, const void* V, void* O, float* LSE
  *                factor -- on the FP8 matrix instruction, sums in float32; the row sum l is of
  *                the rounded P-bar, ones_count counts its unit entries, everything else is
  *                unchanged.  The backward pass has no such mode.
+ *                ATTN_FWD_GUARD_UNDERFLOW: a labelled deviation from Alg. 3, NOT part of the paper
+ *                (which only warns, Sec. 4, that a larger beta risks underflow): the rule is
+ *                skipped -- the tile row keeps its maximum r_m as normaliser, as in Alg. 1 -- where
+ *                it would move the normaliser by more than 60 ((beta-1) r_m > 60 for a positive
+ *                repeated maximum, r_m < -60 for a negative one).  Without the flag such a row
+ *                loses every probability once the move exceeds ~87.3 (the hardware exponential
+ *                returns 0 below 2^-126): l = 0, the row of O is NaN, its LSE is -inf, and a
+ *                backward pass fed with them returns NaN in dQ of that row and in dK / dV of
+ *                every key the row attends to.  fired_count does not count skipped tiles.
  *                Other bits: ATTN_ERR_BAD_ARG.
  * Optional pointers must be 16-byte aligned and must not alias any other argument.
  */
 #define ATTN_FWD_SINGLE_ROUNDING 1u
 #define ATTN_FWD_PV_E4M3 2u
+#define ATTN_FWD_GUARD_UNDERFLOW 4u
 int attn_fwd_opt(const void* Q, const void* K, const void* V, void* O, float* LSE,
                  float* O_hp, int* ones_count, int* fired_count,
                  int B, int H, int N, int d, int causal, float softmax_scale, int variant,

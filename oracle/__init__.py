@@ -9,8 +9,9 @@ Modules
 bf16        software bfloat16 rounding (round-to-nearest, ties-to-even) on numpy arrays
 exact       fp64 attention forward/backward written from the plain definitions
             (Sec. 2.2 of the paper: O = softmax(alpha Q K^T) V, delta, dS, dQ/dK/dV)
-flash       the tiled algorithms (Alg. 1, Alg. 2, Alg. 3 of the paper) taken step by
-            step, with a pluggable working precision and explicit bf16 rounding points
+flash       the tiled algorithms (Alg. 1, Alg. 2, Alg. 3 of the paper: online softmax over key
+            tiles, the recomputing backward, the stabilised normaliser of Sec. 4), with a
+            pluggable working precision and explicit bf16 rounding points
 metrics     error measures used by the parity tests (max-abs, relative L2, mean signed)
 
 Pin status (see tests/test_oracle_*.py, all CPU-only):

@@ -3,7 +3,7 @@
 bfloat16 = 1 sign bit, 8 exponent bits, 7 fraction bits: the top half of an IEEE
 binary32 word (Sec. 2.1 and Appendix B of the paper).  Converting binary32 to
 bfloat16 keeps the upper 16 bits and rounds on the lower 16 with
-round-to-nearest, ties-to-even (Appendix B, step 4).
+round-to-nearest, ties-to-even (the rounding stage of the addition procedure in Appendix B).
 """
 import numpy as np
 
@@ -11,7 +11,7 @@ import numpy as np
 def bf16_bits(x):
     """binary32 array -> uint16 array of bfloat16 bit patterns (RNE).
 
-    Appendix B, step 4: the discarded part is compared with half of the last kept
+    Appendix B, rounding stage: the discarded part is compared with half of the last kept
     bit; above half rounds away, below half truncates, exactly half goes to the
     neighbour whose last kept bit is 0.  NaNs are returned as a quiet NaN.
     """

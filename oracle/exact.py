@@ -55,8 +55,8 @@ def backward(Q, K, V, dO, alpha, causal, delta=None):
         P     = softmax(alpha Q K^T)
         dV    = P^T dO
         dP    = dO V^T
-        delta = rowsum(dO o O)                      (Alg. 2, step 4)
-        dS    = P o (dP - delta)                    (Alg. 2, step 10)
+        delta = rowsum(dO o O)                      (Alg. 2; Claim 1)
+        dS    = P o (dP - delta)                    (Alg. 2; Eq. 2)
         dQ    = alpha dS K ,  dK = alpha dS^T Q     (Eq. 2, Appendix E.2)
 
     `delta` may be supplied to study the effect of a perturbed delta (Eq. 2);

@@ -1,10 +1,14 @@
-"""The paper's tiled algorithms, step by step, in a chosen working precision
+"""The paper's tiled attention (online softmax over key tiles) in a chosen working precision
 (test infrastructure only).
 
-forward()   Alg. 1 (flash-attention forward) and Alg. 3 (the stabilised forward: Alg. 1 plus
-            the three extra steps that pick the normaliser m when a tile row has a repeated
-            maximum, Sec. 4).
-backward()  Alg. 2 (flash-attention backward).
+forward()   the flash-attention forward (Alg. 1): per key tile, a running normaliser m, the
+            unnormalised probabilities P-bar = exp(S - m), their running row sum l and the
+            running unnormalised output, all rescaled when m grows; O = O-bar / l and
+            L = m + log l at the end (Sec. 2.2).  With variant = MITIGATED the normaliser of a
+            tile row follows Sec. 4 (Alg. 3): beta r_m or 0 instead of the tile row maximum r_m
+            when r_m is attained, within eps, more than once.
+backward()  the flash-attention backward (Alg. 2): P = exp(S - L) recomputed per tile pair,
+            delta = rowsum(dO o O), dS = P o (dP - delta), and the three gradient sums.
 
 A `Precision` fixes the arithmetic:
   FP64  every step in binary64, no rounding points.  In this mode the functions must agree
@@ -31,6 +35,11 @@ A `Precision` fixes the arithmetic:
                binary32 dQ, dK accumulators once at the end; dQ, dK, dV are stored as bf16.
         Scores S stay in binary32 and alpha is applied to the binary32 Q K^T (never by
         pre-scaling Q in bf16).
+          (r7) the exponential returns 0 where its result would be a subnormal binary32 number
+               (below 2^-126): Sec. 4 warns that a larger beta risks underflow without fixing
+               where underflow sets in; whether a row loses all of its probabilities (l = 0,
+               0/0) is decided in the arithmetic of the kernels, whose exponential instruction
+               produces no subnormal results.  Sums and products keep subnormals.
 
 Rows of the score matrix are independent in the forward pass, so the query block size B_r has
 no numerical effect there and all rows are processed together; B_c (the key tile) matters for
@@ -54,20 +63,33 @@ class Precision:
     dtype: type
     rnd: Callable
     rnd_pv: Callable = None     # rounding of the two operands of the P-bar V product, if not `rnd`
+    exp: Callable = np.exp      # the exponential of P-bar, of the rescale factor and of P
 
+
+def exp_without_subnormals(x):
+    """exp in binary32 with results below the smallest normal number (2^-126) replaced by 0 (r7)."""
+    y = np.exp(np.asarray(x, dtype=np.float32))
+    return np.where(y < np.float32(2.0 ** -126), np.float32(0.0), y)
+
+
+# Largest shift of the normaliser the optional guard of forward() lets Alg. 3 make (natural-log
+# units): the row maximum then still maps to exp(-60) ~ 9e-27, 27 units above the underflow
+# threshold of (r7), so every probability within e^-27 of the largest survives.
+GUARD_LIMIT = 60.0
 
 FP64 = Precision("fp64", np.float64, lambda x: x)
-BF16 = Precision("bf16", np.float32, round_to_bf16)
+BF16 = Precision("bf16", np.float32, round_to_bf16, None, exp_without_subnormals)
 # The BF16 dataflow with the one product the paper's analysis singles out, P-bar V (Sec. 3.3.2),
 # taken in 8-bit floating point: P-bar and V are rounded to E4M3 (rounding point (r1) moves to that
 # format, V is quantised without a scale factor), the products are summed in binary32, and
 # everything downstream -- (r2) the row sum of the rounded P-bar, (r3), (r4) -- is unchanged.
 # Forward only; an exploration of the paper's future-work remark on FP8, not something it specifies.
-BF16_PV_E4M3 = Precision("bf16, P-bar V in e4m3", np.float32, round_to_bf16, round_to_e4m3)
+BF16_PV_E4M3 = Precision("bf16, P-bar V in e4m3", np.float32, round_to_bf16, round_to_e4m3,
+                         exp_without_subnormals)
 
 
 def _tile_scores(Qw, Kj, alpha, causal, k0, prec, shift=0):
-    """alpha Q K_j^T for key tile starting at column k0 (Alg. 1 step 6), masked entries -inf.
+    """alpha Q K_j^T for the key tile starting at column k0 (Sec. 2.2), masked entries -inf.
     shift = N_k - N_q: the causal mask is aligned at the bottom right (see oracle.exact)."""
     S = (Qw @ Kj.T) * prec.dtype(alpha)
     if causal:
@@ -78,8 +100,13 @@ def _tile_scores(Qw, Kj, alpha, causal, k0, prec, shift=0):
 
 
 def forward(Q, K, V, alpha, causal, variant=STANDARD, beta=2.0, eps=1e-3, Bc=None, prec=BF16,
-            round_obar=True):
+            round_obar=True, guard=False):
     """One head, Alg. 1 (variant 0) or Alg. 3 (variant 1).
+
+    guard=True is a labelled deviation from Alg. 3, not part of the paper: the rule leaves the
+    normaliser at the tile row maximum whenever it would move it by more than GUARD_LIMIT
+    ((beta-1) r_m for a positive repeated maximum, -r_m for a negative one), i.e. where Sec. 4's
+    "risk of underflow" would otherwise turn the row into 0/0.
 
     round_obar=False drops rounding point (r3): the unnormalised output stays in working
     precision until after the division (the experiment of Sec. 3.3.2 in which computing only
@@ -89,7 +116,7 @@ def forward(Q, K, V, alpha, causal, variant=STANDARD, beta=2.0, eps=1e-3, Bc=Non
       O      [N,d]  output (bf16-valued in BF16 mode)
       Ohp    [N,d]  Oacc / l with no rounding at (r3) or (r4): the "O computed in high
                     precision" of Sec. 3.2, from which delta_hp = rowsum(dO o Ohp) is formed
-      L      [N]    logsumexp  m + log l            (Alg. 1 step 12)
+      L      [N]    logsumexp  m + log l
       Obar   [N,d]  unnormalised output after rounding point (r3)
       Oacc   [N,d]  unnormalised output before (r3) (working precision)
       ell,m  [N]    final running sum / normaliser
@@ -101,43 +128,49 @@ def forward(Q, K, V, alpha, causal, variant=STANDARD, beta=2.0, eps=1e-3, Bc=Non
     N, d = Qw.shape
     Nk = Kw.shape[0]
     Bc = Nk if Bc is None else int(Bc)
-    m = np.full(N, -np.inf, dtype=dt)          # Alg. 1 step 4
-    ell = np.zeros(N, dtype=dt)
-    acc = np.zeros((N, d), dtype=dt)
+    m = np.full(N, -np.inf, dtype=dt)          # running normaliser of every row
+    ell = np.zeros(N, dtype=dt)                # running row sum of P-bar
+    acc = np.zeros((N, d), dtype=dt)           # running unnormalised output
     fired = np.zeros(N, dtype=np.int64)
     ones = np.zeros(N, dtype=np.int64)
     with np.errstate(invalid="ignore", over="ignore", divide="ignore"):
-        for k0 in range(0, Nk, Bc):            # Alg. 1 step 5
+        for k0 in range(0, Nk, Bc):
             Kj = Kw[k0:k0 + Bc]; Vj = Vw[k0:k0 + Bc]
-            S = _tile_scores(Qw, Kj, alpha, causal, k0, prec, Nk - N)    # step 6
-            r_m = np.max(S, axis=1)                                       # Alg. 3: tile row max
+            S = _tile_scores(Qw, Kj, alpha, causal, k0, prec, Nk - N)
+            # normaliser proposed by this tile: the tile row maximum r_m, or Sec. 4's choice
+            r_m = np.max(S, axis=1)
             m_prime = r_m
             if variant == MITIGATED:
-                # Alg. 3 extra steps (Sec. 4): count entries within eps of the tile row max;
-                # if more than one, move the normaliser away from the max.
+                # Sec. 4: r_s counts the entries within eps of r_m; more than one of them means
+                # several P-bar would be exactly 1, so the normaliser moves off the maximum:
+                # to beta r_m when r_m > 0, to 0 when r_m < 0 (every P-bar then stays below 1)
                 r_s = np.sum((r_m[:, None] - S) <= dt(eps), axis=1)
                 repeated = r_s > 1
+                if guard:
+                    shift_by = np.where(r_m > 0, (dt(beta) - dt(1.0)) * r_m, -r_m)
+                    repeated = repeated & (shift_by <= dt(GUARD_LIMIT))
                 m_prime = np.where((r_m > 0) & repeated, dt(beta) * r_m, r_m)
                 m_prime = np.where((r_m < 0) & repeated, dt(0.0), m_prime)
                 fired += (m_prime != r_m).astype(np.int64)
-            m_new = np.maximum(m, m_prime.astype(dt))                     # step 7 (running max)
+            m_new = np.maximum(m, m_prime.astype(dt))          # the normaliser only ever grows
             # rows with nothing visible yet have m_new = -inf: they contribute nothing
             safe_m = np.where(np.isneginf(m_new), dt(0.0), m_new)
-            Pbar = np.exp(S - safe_m[:, None]).astype(dt)                 # step 7
+            Pbar = prec.exp(S - safe_m[:, None]).astype(dt)                # (r7)
             rnd_pv = prec.rnd_pv or prec.rnd
-            Phat = rnd_pv(Pbar).astype(dt)                                # (r1)
+            Phat = rnd_pv(Pbar).astype(dt)                                 # (r1)
             if prec.rnd_pv is not None:
                 Vj = prec.rnd_pv(Vj).astype(dt)
-            corr = np.where(np.isneginf(m), dt(0.0), np.exp(m - safe_m)).astype(dt)
-            ell = (corr * ell + np.sum(Phat, axis=1, dtype=dt)).astype(dt)   # step 7, (r2)
-            acc = (corr[:, None] * acc + Phat @ Vj).astype(dt)            # step 8
+            # what was accumulated under the old normaliser is brought to the new one
+            corr = np.where(np.isneginf(m), dt(0.0), prec.exp(m - safe_m)).astype(dt)
+            ell = (corr * ell + np.sum(Phat, axis=1, dtype=dt)).astype(dt)  # (r2)
+            acc = (corr[:, None] * acc + Phat @ Vj).astype(dt)
             ones += np.sum(Phat == dt(1.0), axis=1)
             m = m_new
-        Obar = prec.rnd(acc).astype(dt) if round_obar else acc            # (r3)
+        Obar = prec.rnd(acc).astype(dt) if round_obar else acc             # (r3)
         seen = ~np.isneginf(m)[:, None]       # a query with no visible key (N_q > N_k) outputs 0, L = -inf
-        O = np.where(seen, prec.rnd(Obar / ell[:, None]), dt(0.0)).astype(dt)   # step 10, (r4)
+        O = np.where(seen, prec.rnd(Obar / ell[:, None]), dt(0.0)).astype(dt)   # (r4)
         Ohp = np.where(seen, acc / ell[:, None], dt(0.0)).astype(dt)
-        L = (m + np.log(ell)).astype(dt)                                   # step 11
+        L = (m + np.log(ell)).astype(dt)                                    # row logsumexp
     return {"O": O, "L": L, "Obar": Obar, "Oacc": acc, "ell": ell, "m": m,
             "fired": fired, "ones": ones, "Ohp": Ohp}
 
@@ -145,7 +178,7 @@ def forward(Q, K, V, alpha, causal, variant=STANDARD, beta=2.0, eps=1e-3, Bc=Non
 def backward(Q, K, V, O, dO, L, alpha, causal, Bc=None, Br=None, prec=BF16):
     """One head, Alg. 2.  O and L are the forward pass's outputs (O bf16-valued in BF16 mode).
 
-    O is used for delta = rowsum(dO o O) only (step 4) and is taken as given: passing the
+    O is used for delta = rowsum(dO o O) only and is taken as given: passing the
     forward pass's `Ohp` instead of its bf16 `O` gives delta_hp, the variant of Sec. 3.2 that
     restores stability with everything else unchanged.
 
@@ -159,27 +192,29 @@ def backward(Q, K, V, O, dO, L, alpha, causal, Bc=None, Br=None, prec=BF16):
     Bc = Nk if Bc is None else int(Bc)
     Br = N if Br is None else int(Br)
     Lw = np.where(np.isneginf(Lw), dt(0.0), Lw)     # queries that see no key: every score is -inf, P = 0
-    delta = np.sum(dOw * Ow, axis=1, dtype=dt)                            # Alg. 2 step 4
-    dQ = np.zeros((N, d), dtype=dt)                                       # step 3
+    delta = np.sum(dOw * Ow, axis=1, dtype=dt)        # (r6): from the O handed in
+    dQ = np.zeros((N, d), dtype=dt)
     dK = np.zeros((Nk, d), dtype=dt)
     dV = np.zeros((Nk, d), dtype=dt)
     with np.errstate(invalid="ignore", over="ignore"):
-        for k0 in range(0, Nk, Bc):                                       # step 5
+        for k0 in range(0, Nk, Bc):                    # key tiles outside, query tiles inside
             Kj = Kw[k0:k0 + Bc]; Vj = Vw[k0:k0 + Bc]
-            for q0 in range(0, N, Br):                                    # step 7
+            for q0 in range(0, N, Br):
                 Qi = Qw[q0:q0 + Br]; dOi = dOw[q0:q0 + Br]
-                S = (Qi @ Kj.T) * dt(alpha)                               # step 8
+                S = (Qi @ Kj.T) * dt(alpha)
                 if causal:
                     r = (q0 + np.arange(Qi.shape[0]))[:, None]
                     c = (k0 + np.arange(Kj.shape[0]))[None, :]
                     S = np.where(c > r + (Nk - N), dt(-np.inf), S)
-                P = np.exp(S.astype(dt) - Lw[q0:q0 + Br, None]).astype(dt)   # step 9
-                dV[k0:k0 + Bc] += prec.rnd(P).astype(dt).T @ dOi          # step 10
-                dP = (dOi @ Vj.T).astype(dt)                              # step 11
-                dS = (P * (dP - delta[q0:q0 + Br, None])).astype(dt)      # step 12
-                dSr = prec.rnd(dS).astype(dt)
-                dQ[q0:q0 + Br] += dSr @ Kj                                # step 13
-                dK[k0:k0 + Bc] += dSr.T @ Qi                              # step 14
+                # the probabilities again, from the stored logsumexp (no running statistics)
+                P = prec.exp(S.astype(dt) - Lw[q0:q0 + Br, None]).astype(dt)
+                dV[k0:k0 + Bc] += prec.rnd(P).astype(dt).T @ dOi          # P rounded as an operand only
+                dP = (dOi @ Vj.T).astype(dt)
+                dS = (P * (dP - delta[q0:q0 + Br, None])).astype(dt)      # from the unrounded P
+                dSr = prec.rnd(dS).astype(dt)                             # rounded once, as an operand
+                dQ[q0:q0 + Br] += dSr @ Kj
+                dK[k0:k0 + Bc] += dSr.T @ Qi
+    # alpha belongs to dS (Eq. 2); applied once to the binary32 sums instead
     dQ = prec.rnd(dQ * dt(alpha)).astype(dt)
     dK = prec.rnd(dK * dt(alpha)).astype(dt)
     dV = prec.rnd(dV).astype(dt)
@@ -202,7 +237,7 @@ def delta_recomputed(Q, K, V, dO, L, alpha, causal, Bc=None, prec=BF16):
         for k0 in range(0, Nk, Bc):
             Kj = Kw[k0:k0 + Bc]; Vj = Vw[k0:k0 + Bc]
             S = _tile_scores(Qw, Kj, alpha, causal, k0, prec, Nk - N)
-            P = np.exp(S - Lw[:, None]).astype(dt)
+            P = prec.exp(S - Lw[:, None]).astype(dt)
             dP = (dOw @ Vj.T).astype(dt)
             delta = (delta + np.sum(P * dP, axis=1, dtype=dt)).astype(dt)
     return delta

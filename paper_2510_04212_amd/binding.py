@@ -72,6 +72,7 @@ _lib.attn_fwd_key_tile.restype = _i
 
 FWD_SINGLE_ROUNDING = 1
 FWD_PV_E4M3 = 2
+FWD_GUARD_UNDERFLOW = 4
 
 EXPORTS = ["attn_fwd", "attn_fwd_ex", "attn_fwd_opt", "attn_delta", "attn_delta_hp",
            "attn_delta_recompute", "attn_bwd",
@@ -150,7 +151,7 @@ def attn_fwd(Q, K, V, causal, softmax_scale, variant=STANDARD, beta=None, eps=No
 
 def attn_fwd_opt(Q, K, V, causal, softmax_scale, variant=STANDARD, beta=None, eps=None,
                  want_O_hp=False, want_counts=False, single_rounding=False, pv_e4m3=False,
-                 O=None, LSE=None, stream=None):
+                 guard_underflow=False, O=None, LSE=None, stream=None):
     """attn_fwd_opt of the C ABI: returns a dict with O, LSE and, when asked for, O_hp (float32
     [B,H,N,d]), ones and fired (int32 [B,H,N])."""
     B, H, N, d = _bhnd(Q, "Q")
@@ -170,7 +171,8 @@ def attn_fwd_opt(Q, K, V, causal, softmax_scale, variant=STANDARD, beta=None, ep
                            float(softmax_scale), int(variant),
                            float(DEFAULT_BETA if beta is None else beta),
                            float(DEFAULT_EPS if eps is None else eps),
-                           (FWD_SINGLE_ROUNDING if single_rounding else 0) | (FWD_PV_E4M3 if pv_e4m3 else 0),
+                           (FWD_SINGLE_ROUNDING if single_rounding else 0) | (FWD_PV_E4M3 if pv_e4m3 else 0)
+                           | (FWD_GUARD_UNDERFLOW if guard_underflow else 0),
                            _stream(stream))
     _check(st)
     return out

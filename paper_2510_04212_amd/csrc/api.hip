@@ -86,7 +86,7 @@ static int fwd_entry(const void* Q, const void* K, const void* V, void* O, float
                      int variant, float beta, float eps, unsigned flags, const Layout* user_lay,
                      void* stream) {
   bool empty;
-  if (flags & ~(unsigned)(ATTN_FWD_SINGLE_ROUNDING | ATTN_FWD_PV_E4M3)) return ATTN_ERR_BAD_ARG;
+  if (flags & ~(unsigned)(ATTN_FWD_SINGLE_ROUNDING | ATTN_FWD_PV_E4M3 | ATTN_FWD_GUARD_UNDERFLOW)) return ATTN_ERR_BAD_ARG;
   int st = check_shape(B, H, N, d, &empty);
   if (st != ATTN_OK) return st;
   if (variant < ATTN_VARIANT_STANDARD || variant > ATTN_VARIANT_MITIGATED_ROW) return ATTN_ERR_BAD_ARG;
@@ -106,7 +106,8 @@ static int fwd_entry(const void* Q, const void* K, const void* V, void* O, float
   const Layout lay = user_lay ? *user_lay : contiguous(H, N, d);
   hipError_t e = attn_fwd_dispatch(Q, K, V, O, LSE, B * H, N, d, causal, softmax_scale, variant,
                                    beta, eps, O_hp, ones_count, fired_count,
-                                   ((flags & ATTN_FWD_SINGLE_ROUNDING) ? 1 : 0) | ((flags & ATTN_FWD_PV_E4M3) ? 2 : 0), lay,
+                                   ((flags & ATTN_FWD_SINGLE_ROUNDING) ? 1 : 0) | ((flags & ATTN_FWD_PV_E4M3) ? 2 : 0) |
+                                       ((flags & ATTN_FWD_GUARD_UNDERFLOW) ? 4 : 0), lay,
                                    static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
 }

@@ -27,7 +27,18 @@ struct FwdExtras {
   int* fired;           // [B,H,N]: number of key tiles in which Alg. 3 moved the normaliser, or null
   int single_rounding;  // nonzero: O-bar is NOT rounded to bf16 before the division by l
   int pv_e4m3;          // nonzero: the P-bar V product takes both operands in 8-bit E4M3
+  int guard;            // nonzero: Alg. 3's rule is not applied where it would move the normaliser
+                        // by more than kGuardLimit (a labelled deviation from Sec. 4, see attn.h)
 };
+
+// Largest move of the normaliser the guarded form of Alg. 3 makes, in natural-log units of the
+// alpha-scaled scores: the row maximum then still maps to exp(-60) ~ 9e-27, far above the point
+// where the hardware exponential returns 0 (2^-126).
+constexpr float kGuardLimit = 60.0f;
+DEVI bool guard_allows(float r_m, float beta) {
+  const float shift_by = r_m > 0.f ? (beta - 1.0f) * r_m : -r_m;
+  return shift_by <= kGuardLimit;
+}
 
 // Eight float32 values -> eight E4M3 bytes (hardware conversion: round to nearest even).
 DEVI long pack_e4m3(const float (&v)[8]) {
@@ -214,6 +225,7 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
             // the test  r_m - alpha*s <= eps  in terms of the raw score:  s >= (r_m - eps) / alpha
             // (a row with nothing visible in this tile has r_m = -inf: no rule, no update)
             repeated = second >= (mx * alpha - eps) * inv_alpha && (!RAGGED || mx > -INFINITY);
+            if (EXTRAS && ex.guard != 0) repeated = repeated && guard_allows(mx * alpha, beta);
           } else {
             mx = s[0][0];
 #pragma unroll
@@ -335,7 +347,8 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
     const float M1 = fmaxf(top1, o1);
     const float M2 = fmaxf(fminf(top1, o1), fmaxf(top2, o2));
     const float r_m = M1 * alpha;
-    const bool repeated = (r_m - M2 * alpha) <= eps;      // r_s > 1
+    bool repeated = (r_m - M2 * alpha) <= eps;            // r_s > 1
+    if (EXTRAS && ex.guard != 0) repeated = repeated && guard_allows(r_m, beta);
     float m_row = (repeated && r_m > 0.f) ? beta * r_m : r_m;
     m_row = (repeated && r_m < 0.f) ? 0.f : m_row;
     if (h == 0 && (!RAGGED || q < N)) {
@@ -412,9 +425,9 @@ hipError_t attn_fwd_dispatch(const void* Q, const void* K, const void* V, void* 
                              int BH, int N, int d, int causal, float alpha, int variant,
                              float beta, float eps, float* O_hp, int* ones, int* fired,
                              int flags, Layout lay, hipStream_t st) {
-  // flags: bit 0 = single rounding of the output, bit 1 = P-bar V in E4M3
+  // flags: bit 0 = single rounding of the output, bit 1 = P-bar V in E4M3, bit 2 = guarded Alg. 3
   const bool extras = O_hp != nullptr || ones != nullptr || fired != nullptr || flags != 0;
-  const FwdExtras ex{O_hp, ones, fired, flags & 1, (flags >> 1) & 1};
+  const FwdExtras ex{O_hp, ones, fired, flags & 1, (flags >> 1) & 1, (flags >> 2) & 1};
   if (variant == 2) {   // whole-row detection: statistics pass, then the fixed-normaliser pass
 #define CASE2(DD, CC)                                                                           \
   if (d == DD && (causal != 0) == CC) {                                                          \

@@ -34,9 +34,11 @@ class Workload:
     dup_fraction: float = 0.25  # tied: share of K rows overwritten by a copy of another row
     dup_scope: str = "block"    # tied: copy source within the same aligned 64-row block, or "any"
     q_noise: float = 0.1        # tied: std of the noise added to the low-rank Q
-    q_coef: float = 0.5         # tied: std of Q's rank-2 coefficients (keeps |alpha q.k| below ~70, so
-                                # that (beta-1) * rowmax stays inside binary32's exponent range: the
-                                # stabilised forward underflows otherwise, Sec. 4)
+    q_coef: float = 1.0         # tied: std of Q's rank-2 coefficients.  1.0 is the stress input as
+                                # specified (Q from the same rank-2 subspace as K): row maxima reach
+                                # ~140, where the stabilised forward with beta = 2 underflows in some
+                                # rows (Sec. 4).  0.5 keeps |alpha q.k| below ~70, inside the range
+                                # in which (beta-1) * rowmax leaves every exponential representable.
     skew: bool = False          # V <- -|skew_mu + skew_sigma z|, dO <- -|z|  (one-signed columns)
     skew_mu: float = 0.0
     skew_sigma: float = 1.0
@@ -58,13 +60,20 @@ WORKLOADS = {
     "tiny": Workload("tiny", 1, 1, 128, 64, False, 1001),
     # GPT-2-small attention shape, peaky softmax
     "gpt2s": Workload("gpt2s", 8, 12, 1024, 64, True, 1002, qk_scale=1.5),
-    # repeated-row-maxima stress (rank-2 Q/K, duplicated K rows)
-    "tied": Workload("tied", 4, 12, 1024, 64, True, 1003, kind="tied"),
-    "tied_any": Workload("tied_any", 4, 12, 1024, 64, True, 1003, kind="tied", dup_scope="any"),
-    # same, with one-signed V and dO: the setting in which the rounding bias has a sign
-    "tied_skew": Workload("tied_skew", 4, 12, 1024, 64, True, 1003, kind="tied", skew=True),
+    # repeated-row-maxima stress as specified (rank-2 K with duplicated rows, Q from the same
+    # rank-2 subspace with unit coefficients plus noise); `_skew`: one-signed V and dO, the
+    # setting in which the rounding bias has a sign
+    "tied_q1": Workload("tied_q1", 4, 12, 1024, 64, True, 1003, kind="tied"),
+    "tied_skew_q1": Workload("tied_skew_q1", 4, 12, 1024, 64, True, 1003, kind="tied", skew=True),
+    "tied_any_skew_q1": Workload("tied_any_skew_q1", 4, 12, 1024, 64, True, 1003, kind="tied",
+                                 dup_scope="any", skew=True),
+    # the same with Q's coefficients halved, which keeps every row inside the range the
+    # stabilised forward handles (no underflow)
+    "tied": Workload("tied", 4, 12, 1024, 64, True, 1003, kind="tied", q_coef=0.5),
+    "tied_any": Workload("tied_any", 4, 12, 1024, 64, True, 1003, kind="tied", dup_scope="any", q_coef=0.5),
+    "tied_skew": Workload("tied_skew", 4, 12, 1024, 64, True, 1003, kind="tied", skew=True, q_coef=0.5),
     "tied_any_skew": Workload("tied_any_skew", 4, 12, 1024, 64, True, 1003, kind="tied",
-                              dup_scope="any", skew=True),
+                              dup_scope="any", skew=True, q_coef=0.5),
     # peaky rows whose maximum is attained by exactly two bit-identical keys (retrieval-like
     # heads): every key vector occurs twice in a row (positions 2i, 2i+1), each query is a scaled
     # copy of one visible key plus noise, so its two matching scores tie and every other

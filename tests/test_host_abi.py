@@ -70,7 +70,7 @@ def test_argument_validation_happens_on_the_host(binding):
     ptrs_for_strided = [ctypes.c_void_p(0x1000 * (i + 1)) for i in range(9)]
     ws_for_strided = ctypes.c_void_p(0x100000)
     opt = lambda ohp, ones, fired, flags=0, O=q: lib.attn_fwd_opt(p, p, p, O, p, ohp, ones, fired, 1, 1, 128, 64, 1, 0.125, 0, 2.0, 1e-3, flags, None)
-    assert opt(None, None, None, flags=4) == BAD                 # unknown flag bit
+    assert opt(None, None, None, flags=8) == BAD                 # unknown flag bit
     assert opt(mis, None, None) == BAD                           # misaligned optional output
     assert opt(q, None, None) == BAD                             # O_hp aliases O
     r_ = ctypes.c_void_p(0x3000)

@@ -292,3 +292,148 @@ def test_fp8_product_mode_only_touches_the_two_operands_of_pbar_v():
     a = flash.forward(Q, K2, V2, 0.4, True, flash.STANDARD, prec=flash.BF16_PV_E4M3)
     b = flash.forward(Q, K2, V2, 0.4, True, flash.STANDARD, prec=flash.BF16)
     assert np.array_equal(a["O"], b["O"])
+
+
+def _all_orders_exact(terms):
+    """True when summing `terms` in binary32 gives the same bits in ANY order: every term is a
+    multiple of one quantum q and sum |terms| < 2^24 q, so no partial sum ever needs rounding."""
+    t = np.asarray(terms, dtype=np.float64).ravel()
+    t = t[t != 0]
+    if t.size == 0:
+        return True
+    low = []                                     # value of the lowest set bit of every term
+    for v in np.abs(t):
+        mant, e = np.frexp(v)                    # v = mant * 2^e, mant in [0.5, 1) with <= 53 bits
+        k = int(mant * 2.0 ** 53)
+        low.append(2.0 ** (e - 53) * (k & -k))
+    q = min(low)                                 # every term is a multiple of q
+    return bool(np.sum(np.abs(t)) < 2.0 ** 24 * q)
+
+
+def test_bf16_backward_rounding_points_by_hand():
+    """The bf16-mode backward on one small tile against a hand evaluation with explicit loops and
+    the rounding points of reading (r6) written where they belong: delta from the bf16 O; P in
+    binary32, rounded to bf16 only as the operand of P^T dO; dS = P o (dP - delta) from the
+    UNROUNDED P, rounded to bf16 once as the operand of dS K and dS^T Q; binary32 sums; alpha
+    applied once to the finished sums; outputs rounded to bf16.  The inputs are chosen so that
+    every sum is exact in binary32 in any order (checked), hence bit-for-bit equality.  Four
+    planted mistakes -- P rounded before dS is formed, the operand rounding of P dropped, the
+    rounding of dS dropped, alpha applied before the accumulation -- must each change a result."""
+    from oracle.bf16 import round_to_bf16 as rnd
+    f32 = np.float32
+    rng = np.random.default_rng(2)
+    Nq, Nk, d, alpha = 6, 5, 4, 0.3
+    Q = rng.integers(-2, 3, size=(Nq, d)).astype(f32)
+    K = rng.integers(-2, 3, size=(Nk, d)).astype(f32)
+    V = (rng.integers(-4, 5, size=(Nk, d)) / 2.0).astype(f32)
+    dO = (rng.integers(-4, 5, size=(Nq, d)) / 4.0).astype(f32)
+    fwd = flash.forward(Q, K, V, alpha, False, flash.STANDARD)
+    O, L = fwd["O"], fwd["L"]
+    got = flash.backward(Q, K, V, O, dO, L, alpha, False)
+
+    # scores and probabilities, entry by entry (integer dot products: exact)
+    S = np.zeros((Nq, Nk), dtype=f32)
+    for i in range(Nq):
+        for j in range(Nk):
+            acc = f32(0)
+            for c in range(d):
+                acc = f32(acc + Q[i, c] * K[j, c])
+            S[i, j] = f32(acc * f32(alpha))
+    P = flash.BF16.exp(S - L[:, None]).astype(f32)           # the same elementwise routine, same shape
+
+    def evaluate(p_for_ds, p_operand, ds_operand, alpha_early):
+        delta = np.zeros(Nq, dtype=f32)
+        for i in range(Nq):
+            terms = [f32(dO[i, c] * O[i, c]) for c in range(d)]
+            assert _all_orders_exact(terms)
+            for t in terms:
+                delta[i] = f32(delta[i] + t)
+        dP = np.zeros((Nq, Nk), dtype=f32)
+        for i in range(Nq):
+            for j in range(Nk):
+                for c in range(d):
+                    dP[i, j] = f32(dP[i, j] + dO[i, c] * V[j, c])
+        dS = np.zeros((Nq, Nk), dtype=f32)
+        for i in range(Nq):
+            for j in range(Nk):
+                dS[i, j] = f32(p_for_ds[i, j] * f32(dP[i, j] - delta[i]))
+        if alpha_early:
+            dS = (dS * f32(alpha)).astype(f32)
+        dSo = ds_operand(dS)
+        Po = p_operand(P)
+        dQ = np.zeros((Nq, d), dtype=f32); dK = np.zeros((Nk, d), dtype=f32); dV = np.zeros((Nk, d), dtype=f32)
+        exact_sums = True
+        for c in range(d):
+            for i in range(Nq):
+                terms = [f32(dSo[i, j] * K[j, c]) for j in range(Nk)]
+                exact_sums &= _all_orders_exact(terms)
+                for t in terms:
+                    dQ[i, c] = f32(dQ[i, c] + t)
+            for j in range(Nk):
+                terms = [f32(dSo[i, j] * Q[i, c]) for i in range(Nq)]
+                exact_sums &= _all_orders_exact(terms)
+                for t in terms:
+                    dK[j, c] = f32(dK[j, c] + t)
+                terms = [f32(Po[i, j] * dO[i, c]) for i in range(Nq)]
+                exact_sums &= _all_orders_exact(terms)
+                for t in terms:
+                    dV[j, c] = f32(dV[j, c] + t)
+        if not alpha_early:
+            dQ = (dQ * f32(alpha)).astype(f32); dK = (dK * f32(alpha)).astype(f32)
+        return rnd(dQ), rnd(dK), rnd(dV), delta, exact_sums
+
+    keep = lambda x: x
+    dQ, dK, dV, delta, exact_sums = evaluate(P, rnd, rnd, False)          # reading (r6)
+    assert exact_sums, "choose inputs whose sums are exact in any order"
+    assert np.array_equal(got[0], dQ) and np.array_equal(got[1], dK) and np.array_equal(got[2], dV)
+    assert np.array_equal(got[3], delta)
+    # planted mistakes: each must be visible in at least one gradient
+    for name, args in (("P rounded before dS", (rnd(P), rnd, rnd, False)),
+                       ("operand rounding of P dropped", (P, keep, rnd, False)),
+                       ("rounding of dS dropped", (P, rnd, keep, False)),
+                       ("alpha before the accumulation", (P, rnd, rnd, True))):
+        m = evaluate(*args)
+        assert not (np.array_equal(got[0], m[0]) and np.array_equal(got[1], m[1]) and np.array_equal(got[2], m[2])), name
+    # and delta really is taken from the bf16 O: the unrounded output gives another delta
+    assert not np.array_equal(delta, np.sum(dO * fwd["Ohp"], axis=1, dtype=f32))
+
+
+def test_alg3_underflow_threshold_and_the_guard():
+    """Sec. 4 warns that a larger beta risks underflow.  With a repeated positive maximum r_m the
+    largest probability is exp(-(beta-1) r_m); reading (r7) puts the loss of the whole row (l = 0,
+    0/0) where that number drops below 2^-126, i.e. at (beta-1) r_m = 126 ln 2 = 87.34.  The
+    guarded form (a labelled deviation) keeps Alg. 1's normaliser beyond a move of 60 and is
+    Alg. 3 itself below it."""
+    N, d = 8, 4
+    rng = np.random.default_rng(5)
+    V = rng.standard_normal((N, d))
+    want = 0.5 * (V[0] + V[1])                       # two equal maxima, every other key ~e^-r_m away
+    for r_m, lost in ((40.0, False), (59.0, False), (61.0, False), (86.0, False), (87.0, False),
+                      (87.5, True), (92.0, True), (120.0, True)):
+        Q = np.zeros((N, d)); K = np.zeros((N, d))
+        Q[:, 0] = r_m / 8.0; K[0, 0] = 8.0; K[1, 0] = 8.0
+        f = flash.forward(Q, K, V, 1.0, False, flash.MITIGATED, beta=2.0)
+        assert (f["fired"] == 1).all()
+        assert bool((f["ell"] == 0).all()) == lost and bool(np.isnan(f["O"]).all()) == lost, r_m
+        assert bool(np.isneginf(f["L"]).all()) == lost
+        if not lost:
+            assert np.allclose(f["O"], want, atol=2e-2)
+            assert np.allclose(f["L"], r_m + np.log(2.0), atol=5e-3)          # shift invariance survives (P-bar is a bf16 number)
+        g = flash.forward(Q, K, V, 1.0, False, flash.MITIGATED, beta=2.0, guard=True)
+        s = flash.forward(Q, K, V, 1.0, False, flash.STANDARD)
+        assert np.isfinite(g["O"]).all() and np.allclose(g["O"], want, atol=2e-2)
+        if r_m > flash.GUARD_LIMIT:
+            assert (g["fired"] == 0).all() and np.array_equal(g["O"], s["O"]) and (g["ones"] == 2).all()
+        else:
+            assert np.array_equal(g["O"], f["O"]) and np.array_equal(g["fired"], f["fired"])
+    # negative repeated maximum: the normaliser moves to 0, the largest probability is exp(r_m)
+    for r_m, lost in ((-50.0, False), (-87.0, False), (-87.5, True)):
+        Q = np.zeros((N, d)); K = np.zeros((N, d))
+        Q[:, 0] = 1.0; K[:, 0] = 4.0 * r_m; K[0, 0] = r_m; K[1, 0] = r_m
+        f = flash.forward(Q, K, V, 1.0, False, flash.MITIGATED, beta=2.0)
+        assert bool(np.isnan(f["O"]).all()) == lost, r_m
+        g = flash.forward(Q, K, V, 1.0, False, flash.MITIGATED, beta=2.0, guard=True)
+        assert np.isfinite(g["O"]).all() and np.allclose(g["O"], want, atol=2e-2)
+    # fp64 mode has no (r7): the definition's result for every r_m
+    f = flash.forward(Q, K, V, 1.0, False, flash.MITIGATED, beta=2.0, prec=flash.FP64)
+    assert np.allclose(f["O"], want, atol=1e-12)
