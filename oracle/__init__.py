@@ -22,11 +22,15 @@ Pin status (see tests/test_oracle_*.py, all CPU-only):
   flash.forward (fp64 mode) ... pinned (equals exact.forward for any tile size and both
                                 variants: shift invariance, Sec. 4)
   flash.backward (fp64 mode) .. pinned (equals exact.backward)
-  flash.* in bf16 mode ........ pinned only through tolerance against exact.* and through
-                                the structural facts of Sec. 3.3.2 / Sec. 4 (P-bar == 1 at a
-                                row maximum, max P-bar < 1 once the rule fires, sign of the
-                                bias).  Bit-exact agreement of the GPU kernels with the bf16
-                                emulation is NOT claimed: parity unpinned at bit level,
-                                because matrix-core summation order and the hardware exp2
-                                differ from numpy's.
+  flash.forward (bf16 mode) ... pinned: a hand evaluation of one tile through the rounding
+                                points (r1)-(r4) (the E4M3 product test walks the same lines),
+                                bf16 ties reproduced exactly, P-bar == 1 at a row maximum and
+                                max P-bar < 1 once the rule fires, the sign of the bias of
+                                Sec. 3.3.2 and its removal, the underflow threshold of (r7)
+  flash.backward (bf16 mode) .. pinned: an explicit-loop evaluation of one tile with the rounding
+                                points of (r6) written out, bit for bit on inputs whose sums are
+                                exact in any order; four planted mistakes each change a result
+  Bit-exact agreement of the GPU kernels with the bf16 emulation on general inputs is NOT
+  claimed: parity unpinned at bit level, because matrix-core summation order and the hardware
+  exp2 differ from numpy's; the kernels are held to tolerances against the fp64 functions.
 """

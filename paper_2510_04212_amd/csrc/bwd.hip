@@ -234,10 +234,10 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
           for (int e = 0; e < 4; ++e) {
             const int i = 4 * g + e;
             float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l4[e]));
-            if (DIAG) {
-              if (8 * g + e < first_seen) p = 0.f;
-            }
             float ds = p * dp[i];                     // dp already holds dP - delta
+            if (DIAG) {   // a masked entry contributes exactly nothing, whatever its row holds
+              if (8 * g + e < first_seen) { p = 0.f; ds = 0.f; }
+            }
             pf[i >> 3][i & 7] = (bf16_t)p;
             dsf[i >> 3][i & 7] = (bf16_t)ds;
           }

@@ -9,6 +9,12 @@ probability ~1e-6, one-signed V).  On the rank-2 `tied*` inputs both variants si
 noise floor (symmetric V: exactly zero expected bias; one-signed V: rows are not peaky enough
 unless the scores reach the range where the stabilised normaliser underflows), which is
 asserted as such; their numbers are printed.
+
+The stress input AS SPECIFIED (`tied_q1`, `tied_skew_q1`: Q's rank-2 coefficients at 1.0, row
+maxima up to ~140) is where Alg. 3 with beta = 2 meets its own limit (Sec. 4: "larger values risk
+underflow"): some rows lose every probability.  test_tied_max_stress_as_specified pins what the
+kernels do there -- which rows are lost, what that does to the gradients, what the guarded form
+does instead -- against the oracle, and states the signed errors as they are.
 """
 import numpy as np
 import pytest
@@ -71,23 +77,13 @@ def test_bias_and_its_removal_on_paired_keys_one_signed_values(lib):
     # mitigated one).  Both stay three orders of magnitude below the values (|dV| ~ 1..10).
     for v in (0, 1):
         assert abs(st[v]["dV_mean"]) < 1e-3
-    # element-wise parity of O and dV on sampled heads (dQ, dK are pure rounding noise here: the exact
-    # dQ is ~1e-3 because the softmax is one-hot on a tied pair, so they are compared with the
-    # oracle's bf16 emulation of the same dataflow instead)
+    # element-wise parity on sampled heads.  The exact dQ is ~1e-3 here (the softmax is one-hot on a
+    # tied pair), so dQ and dK are rounding noise of the dataflow, and O, dV have magnitudes of 2-10
+    # (bf16 half-ulp 0.8e-2 .. 3e-2): the cases that cannot meet 2e-2 / 1e-2 are in
+    # test_gpu_parity.WIDENED with the emulation's own error.
     for variant in (0, 1):
         for (b, h) in [(0, 0), (3, 11)]:
-            xs = head_np(x, b, h)
-            ref = exact.forward_backward(xs["Q"], xs["K"], xs["V"], xs["dO"], w.alpha, True)
-            f = flash.forward(xs["Q"], xs["K"], xs["V"], w.alpha, True, variant, Bc=lib.fwd_key_tile(w.d))
-            g = flash.backward(xs["Q"], xs["K"], xs["V"], f["O"], xs["dO"], f["L"], w.alpha, True, Bc=64)
-            for name, r in (("O", ref[0]), ("dV", ref[4])):
-                a = got[variant][name][b, h].double().cpu().numpy()
-                assert metrics.rel_l2(a, r) <= 1e-2, name
-                assert np.max(np.abs(a - r) / np.maximum(1.0, np.abs(r))) <= 2e-2, name
-            for name, e, r in (("dQ", g[0], ref[2]), ("dK", g[1], ref[3])):
-                a = got[variant][name][b, h].double().cpu().numpy()
-                assert np.isfinite(a).all()
-                assert metrics.max_abs(a, r) <= 2.0 * metrics.max_abs(e, r) + 2e-2, name
+            check_head(got[variant], x, b, h, w.causal, w.alpha, variant, label=f"pairs_skew v{variant}")
 
 
 def test_symmetric_values_have_no_signed_bias(lib):
@@ -111,4 +107,95 @@ def test_rank2_tied_inputs_reported_and_within_tolerance(lib, name):
         # no variant shows a bias beyond a few standard errors on these inputs
         assert abs(st[v]["O_mean"]) < 8 * st[v]["O_noise"] + 2e-5
     for variant in (0, 1):
-        check_head(got[variant], x, 1, 3, w.causal, w.alpha, variant, label=name)
+        check_head(got[variant], x, 1, 3, w.causal, w.alpha, variant, label=f"{name} v{variant}")
+
+
+def _np(t):
+    return t.double().cpu().numpy()
+
+
+@pytest.mark.parametrize("name", ["tied_q1", "tied_skew_q1"])
+def test_tied_max_stress_as_specified(lib, name):
+    """Rank-2 K with 25 % duplicated rows, Q from the same subspace with unit coefficients.
+    Standard forward: nothing is lost.  Stabilised forward, beta = 2: rows whose repeated maximum
+    r_m exceeds 126 ln 2 / (beta - 1) = 87.3 lose every probability (l = 0): O is NaN, LSE = -inf,
+    and the backward pass turns that into NaN in dQ of the row and in dK, dV of every key the row
+    attends to.  The lost rows, and the counts of unit probabilities and of rule firings, must be
+    the emulation's, row by row, over all heads.  The guarded form loses nothing."""
+    w = synth.WORKLOADS[name]
+    x = synth.make(w, DEV)
+    B, H, N, d = x["Q"].shape
+    runs = {}
+    for key, variant, guard in (("standard", 0, False), ("mitigated", 1, False), ("guarded", 1, True)):
+        r = lib.attn_fwd_opt(x["Q"], x["K"], x["V"], w.causal, w.alpha, variant, want_counts=True,
+                             guard_underflow=guard)
+        r["dQ"], r["dK"], r["dV"] = lib.attn_bwd(x["Q"], x["K"], x["V"], r["O"], x["dO"], r["LSE"],
+                                                 w.causal, w.alpha, variant)
+        r["delta"] = lib.attn_delta(r["O"], x["dO"])
+        runs[key] = r
+    torch.cuda.synchronize()
+    finite = lambda t: torch.isfinite(t.float())
+    for key in ("standard", "guarded"):
+        assert not torch.isneginf(runs[key]["LSE"]).any(), key
+        for n in ("O", "dQ", "dK", "dV", "LSE", "delta"):
+            assert finite(runs[key][n]).all(), (key, n)
+    mit = runs["mitigated"]
+    lost = torch.isneginf(mit["LSE"])                                   # [B,H,N]
+    assert 20 <= int(lost.sum()) <= 200 and int(lost.any(-1).sum()) >= 8      # this input does reach the limit
+    assert torch.equal(torch.isnan(mit["O"].float()).all(-1), lost)     # a lost row is NaN in every column
+    assert torch.equal((~finite(mit["O"])).any(-1), lost) and torch.equal((~finite(mit["dQ"])).any(-1), lost)
+    # dK, dV: NaN exactly in the keys some lost row attends to (causal: keys up to the last lost row)
+    idx = torch.arange(N, device=DEV).expand(B, H, N)
+    last_lost = torch.where(lost, idx, torch.full_like(idx, -1)).max(-1, keepdim=True).values
+    for n in ("dK", "dV"):
+        assert torch.equal((~finite(mit[n])).any(-1), idx <= last_lost), n
+    # row by row against the emulation, every head
+    mismatch = {"lost": 0, "fired": 0, "ones": 0, "fired_guarded": 0}
+    err = {k: {n: [] for n in ("O", "delta", "dQ", "dK", "dV")} for k in runs}
+    for b in range(B):
+        for h in range(H):
+            xs = head_np(x, b, h)
+            f = flash.forward(xs["Q"], xs["K"], xs["V"], w.alpha, True, 1, Bc=lib.fwd_key_tile(d))
+            g = flash.forward(xs["Q"], xs["K"], xs["V"], w.alpha, True, 1, Bc=lib.fwd_key_tile(d), guard=True)
+            mismatch["lost"] += int((_np(lost[b, h]).astype(bool) != (f["ell"] == 0)).sum())
+            mismatch["fired"] += int((_np(mit["fired"][b, h]) != f["fired"]).sum())
+            mismatch["ones"] += int((_np(mit["ones"][b, h]) != f["ones"]).sum())
+            mismatch["fired_guarded"] += int((_np(runs["guarded"]["fired"][b, h]) != g["fired"]).sum())
+            assert np.isfinite(g["O"]).all()
+            ref = dict(zip(("O", "L", "dQ", "dK", "dV", "delta"),
+                           exact.forward_backward(xs["Q"], xs["K"], xs["V"], xs["dO"], w.alpha, True)))
+            for key, r in runs.items():
+                for n in err[key]:
+                    e = _np(r[n][b, h]) - ref[n]
+                    err[key][n].append(e[np.isfinite(e)].ravel())
+    print(f"\n[{name}] lost rows {int(lost.sum())} in {int(lost.any(-1).sum())} heads; row mismatches vs emulation {mismatch}")
+    assert mismatch["lost"] == 0
+    rows = B * H * N
+    assert mismatch["fired"] <= 0.01 * rows and mismatch["ones"] <= 0.01 * rows and mismatch["fired_guarded"] <= 0.01 * rows
+    st = {}
+    for key in runs:
+        st[key] = {}
+        for n in err[key]:
+            e = np.concatenate(err[key][n])
+            st[key][n] = (float(e.mean()), float(e.std() / np.sqrt(e.size)))
+        print(f"   {key:9s} mean signed error vs fp64 (finite entries): " +
+              "  ".join(f"{n} {m:+.2e}+-{s_:.0e}" for n, (m, s_) in st[key].items()))
+    # As they are: the standard forward's mean error of O is within 1e-5 of zero here (rows peaky
+    # enough for the mechanism of Sec. 3.3.2 are the ones with maxima near 100), two orders of
+    # magnitude below its -2e-3 on `pairs_skew`; the guarded stabilised forward is at the same
+    # level; the unguarded one is NOT better on this input: the rows that survive just below the
+    # limit keep only a few significant bits.
+    for key in ("standard", "guarded"):
+        assert abs(st[key]["O"][0]) < 2e-5, key
+        assert abs(st[key]["dV"][0]) < 2e-4 and abs(st[key]["dQ"][0]) < 1e-4 and abs(st[key]["dK"][0]) < 1e-4, key
+    if name == "tied_skew_q1":
+        assert abs(st["mitigated"]["O"][0]) > 5 * abs(st["standard"]["O"][0])      # worse, not better
+    # element-wise parity of the two finite variants on sampled heads.  The gradients reach
+    # magnitudes of several hundred here (scores up to ~140), where a bf16 output cannot be within
+    # 2e-2: the bound for each tensor is the larger of the stated tolerance and what the
+    # low-precision dataflow itself does on this input (the emulation's error), as listed in
+    # test_gpu_parity.WIDENED.
+    for key, variant, guard in (("standard", 0, False), ("guarded", 1, True)):
+        got = dict(runs[key]); got["L"] = got["LSE"]
+        for (b, h) in [(0, 0), (2, 7)]:
+            check_head(got, x, b, h, w.causal, w.alpha, variant, guard=guard, label=f"{name}/{key}")
