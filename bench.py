@@ -58,7 +58,7 @@ def main():
 
     import numpy as np
     import torch
-    from paper_2510_04212_amd import binding, synth
+    from paper_2510_04212_amd import binding, probe, synth
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -199,7 +199,7 @@ def main():
 
     # what the matrix cores sustain on this chip: a loop of matrix instructions on register
     # operands (attn_probe_matrix_clock), ~3 ms on every SIMD
-    probe = binding.probe_matrix_clock(workgroups=512, iters=25000)
+    probe = probe.matrix_clock(workgroups=512, iters=25000)
     out["matrix_core_probe"] = {"shader_clock_ghz": round(probe["shader_clock_ghz"], 3),
                                 "measured_mfma_tflops": round(probe["tflops"], 1),
                                 "frac_of_measured_mfma_rate": round(tflops / probe["tflops"], 4),
@@ -208,8 +208,8 @@ def main():
 
     # and what the LDS delivers: every matrix instruction of the three kernels takes one fresh
     # 1 KB operand fragment from LDS, as one ds_read_b128 or as two transposing ds_read_b64_tr_b16
-    lds128 = binding.probe_lds_clock(kind=0, workgroups=256, iters=20000)
-    ldstr = binding.probe_lds_clock(kind=1, workgroups=256, iters=20000)
+    lds128 = probe.lds_clock(kind=0, workgroups=256, iters=20000)
+    ldstr = probe.lds_clock(kind=1, workgroups=256, iters=20000)
     out["lds_probe"] = {"ds_read_b128_bytes_per_clk_per_cu": round(lds128["bytes_per_clk_per_cu"], 1),
                         "ds_read_b64_tr_b16_bytes_per_clk_per_cu": round(ldstr["bytes_per_clk_per_cu"], 1),
                         "note": "read-only loops, 4 waves per CU: one wave-wide LDS read instruction per 4 clocks and CU "

@@ -268,30 +268,6 @@ int attn_bwd_rect(const void* Q, const void* K, const void* V, const void* O, co
                   int B, int H, int Nq, int Nk, int d, int causal, float softmax_scale, int variant,
                   void* stream);
 
-/*
- * Measurement aid for benchmarks (no attention arithmetic, nothing from the paper): runs
- * `workgroups` work-groups of 4 waves, each wave issuing 4 * iters independent
- * v_mfma_f32_32x32x16_bf16 instructions on register operands, and writes to the DEVICE array
- * out[0..2] (16-byte aligned, 3 x int64): out[0] = shader-clock cycles and out[1] = ticks of the
- * constant 100 MHz counter that the first wave spent in its loop (out[2] is scratch).
- * out[0] / (out[1] / 1e8) is the shader clock sustained under matrix load; the caller times the
- * launch to get the instruction rate.  1 <= workgroups <= 65536, 1 <= iters <= 2^22
- * (ATTN_ERR_BAD_ARG otherwise).  Enqueued on `stream` like everything else.
- */
-int attn_probe_matrix_clock(long long* out, int workgroups, int iters, void* stream);
-
-/*
- * The same kind of measurement aid for the LDS: `workgroups` work-groups of 4 waves, each wave
- * issuing 16 * iters conflict-free LDS reads and nothing else; kind 0: ds_read_b128 (1 KB per
- * instruction, the size of one matrix-instruction operand fragment), kind 1: ds_read_b64_tr_b16
- * (the transposing read, 512 bytes per instruction).  out[0..2] as above (shader-clock cycles
- * and 100 MHz ticks of the first wave's loop, scratch).  With one work-group per CU,
- * 4 waves * 16 * iters * bytes-per-instruction / out[0] is the LDS read bandwidth of a CU in
- * bytes per clock.  kind outside {0, 1}: ATTN_ERR_BAD_ARG; otherwise the argument limits and
- * errors of attn_probe_matrix_clock.
- */
-int attn_probe_lds_clock(long long* out, int kind, int workgroups, int iters, void* stream);
-
 /* Human-readable name of an attn_status (static storage, never NULL). */
 const char* attn_status_string(int status);
 

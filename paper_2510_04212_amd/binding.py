@@ -51,10 +51,6 @@ _lib.attn_fwd_rect.argtypes = [_vp] * 5 + [_i, _i, _i, _i, _i, _i, _f, _i, _f, _
 _lib.attn_fwd_rect.restype = _i
 _lib.attn_bwd_rect.argtypes = [_vp] * 9 + [_vp, _sz, _i, _i, _i, _i, _i, _i, _f, _i, _vp]
 _lib.attn_bwd_rect.restype = _i
-_lib.attn_probe_matrix_clock.argtypes = [_vp, _i, _i, _vp]
-_lib.attn_probe_matrix_clock.restype = _i
-_lib.attn_probe_lds_clock.argtypes = [_vp, _i, _i, _i, _vp]
-_lib.attn_probe_lds_clock.restype = _i
 _lib.attn_bwd.argtypes = [_vp] * 9 + [_vp, _sz, _i, _i, _i, _i, _i, _f, _i, _vp]
 _lib.attn_bwd.restype = _i
 _lib.attn_bwd_dkdv.argtypes = [_vp] * 8 + [_i, _i, _i, _i, _i, _f, _vp]
@@ -79,7 +75,7 @@ EXPORTS = ["attn_fwd", "attn_fwd_ex", "attn_fwd_opt", "attn_delta", "attn_delta_
            "attn_bwd_dkdv", "attn_bwd_dq", "attn_bwd_dq_delta", "attn_fwd_strided", "attn_bwd_strided",
            "attn_fwd_gqa", "attn_bwd_gqa", "attn_fwd_rect", "attn_bwd_rect",
            "attn_bwd_workspace_bytes",
-           "attn_status_string", "attn_fwd_key_tile", "attn_probe_matrix_clock", "attn_probe_lds_clock"]
+           "attn_status_string", "attn_fwd_key_tile"]
 
 
 class AttnError(RuntimeError):
@@ -384,41 +380,3 @@ def attn_bwd_rect(Q, K, V, O, dO, LSE, causal, softmax_scale, variant=STANDARD, 
                               _ptr(dV), _ptr(workspace), workspace.numel(), B, H, Nq, Nk, d,
                               int(bool(causal)), float(softmax_scale), int(variant), _stream(stream)))
     return dQ, dK, dV
-
-
-def probe_matrix_clock(workgroups=512, iters=50000, stream=None):
-    """Runs the library's matrix-instruction loop (attn_probe_matrix_clock) and returns a dict:
-    shader clock in GHz sustained under matrix load, elapsed milliseconds of the launch, and the
-    matrix-instruction rate in TFLOP/s (4 waves x 4 iters instructions of 32768 FLOP per work-group)."""
-    out = torch.zeros(4, dtype=torch.int64, device="cuda")
-    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
-    s = torch.cuda.current_stream() if stream is None else stream
-    e0.record(s)
-    _check(_lib.attn_probe_matrix_clock(_ptr(out), int(workgroups), int(iters), _stream(stream)))
-    e1.record(s)
-    e1.synchronize()
-    ms = e0.elapsed_time(e1)
-    cyc, ticks = out[0].item(), out[1].item()
-    flop = float(workgroups) * 4 * 4 * iters * 32768.0
-    return {"shader_clock_ghz": cyc / (ticks / 1e8) / 1e9 if ticks else float("nan"),
-            "ms": ms, "tflops": flop / (ms * 1e-3) / 1e12}
-
-
-def probe_lds_clock(kind=0, workgroups=256, iters=20000, stream=None):
-    """Runs the library's LDS read loop (attn_probe_lds_clock; kind 0: ds_read_b128, kind 1:
-    ds_read_b64_tr_b16), by default one work-group per CU, and returns a dict: LDS read bandwidth
-    in bytes per shader clock and CU as seen by the first wave's own clock, and the aggregate
-    rate in TB/s from the launch time."""
-    out = torch.zeros(4, dtype=torch.int64, device="cuda")
-    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
-    s = torch.cuda.current_stream() if stream is None else stream
-    e0.record(s)
-    _check(_lib.attn_probe_lds_clock(_ptr(out), int(kind), int(workgroups), int(iters), _stream(stream)))
-    e1.record(s)
-    e1.synchronize()
-    ms = e0.elapsed_time(e1)
-    cyc, ticks = out[0].item(), out[1].item()
-    per_wg = 4 * 16 * float(iters) * (1024.0 if kind == 0 else 512.0)
-    return {"bytes_per_clk_per_cu": per_wg / cyc if cyc else float("nan"),
-            "shader_clock_ghz": cyc / (ticks / 1e8) / 1e9 if ticks else float("nan"),
-            "ms": ms, "TB/s": per_wg * workgroups / (ms * 1e-3) / 1e12}

@@ -1,8 +1,9 @@
 """Builds the HIP library in-tree:  python -m paper_2510_04212_amd.build
 
-One hipcc invocation per source (gfx950 only), linked into
-paper_2510_04212_amd/libattn_gfx950.so.  Packed-fp32 code generation is switched off for all
-device code.
+One hipcc invocation per source (gfx950 only).  Two libraries come out:
+  libattn_gfx950.so         the attention library (the C ABI of include/attn.h);
+  libattn_probe_gfx950.so   measurement aids that only the benchmark loads (csrc/probe.h).
+Packed-fp32 code generation is switched off for all device code.
 """
 import os
 import subprocess
@@ -11,7 +12,9 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libattn_gfx950.so")
-SOURCES = ["api.hip", "fwd.hip", "delta.hip", "bwd.hip", "probe.hip"]
+PROBE_LIB = os.path.join(HERE, "libattn_probe_gfx950.so")
+SOURCES = ["api.hip", "fwd.hip", "delta.hip", "bwd.hip"]
+PROBE_SOURCES = ["probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument",
@@ -31,7 +34,7 @@ def build(verbose=True):
     os.makedirs(objdir, exist_ok=True)
     objs = []
     procs = []
-    for src in SOURCES:
+    for src in SOURCES + PROBE_SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         cmd = [hipcc] + FLAGS + EXTRA_FLAGS.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
@@ -45,10 +48,11 @@ def build(verbose=True):
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
         if verbose and out.strip():
             print(out)
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+    for lib, n0, n1 in ((LIB, 0, len(SOURCES)), (PROBE_LIB, len(SOURCES), len(objs))):
+        cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + objs[n0:n1]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
     return LIB
 
 

@@ -30,9 +30,6 @@ hipError_t attn_delta_recompute_dispatch(const void*, const void*, const void*, 
                                          const float*, float*, int, int, int, int, float, Layout,
                                          hipStream_t);
 
-hipError_t attn_probe_dispatch(long long*, int, int, hipStream_t);
-hipError_t attn_probe_lds_dispatch(long long*, int, int, int, hipStream_t);
-
 namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -373,21 +370,4 @@ extern "C" int attn_bwd_rect(const void* Q, const void* K, const void* V, const 
   const Layout lay = (B > 0 && H > 0) ? contiguous(H, Nq, d, 0, Nk) : contiguous(1, 1, d);
   return bwd_entry(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, H, Nq, d, causal,
                    softmax_scale, variant, &lay, stream);
-}
-
-extern "C" int attn_probe_lds_clock(long long* out, int kind, int workgroups, int iters, void* stream) {
-  if (kind < 0 || kind > 1) return ATTN_ERR_BAD_ARG;
-  if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 22)) return ATTN_ERR_BAD_ARG;
-  if (!out) return ATTN_ERR_NULL;
-  if (!aligned16(out)) return ATTN_ERR_BAD_ARG;
-  hipError_t e = attn_probe_lds_dispatch(out, kind, workgroups, iters, static_cast<hipStream_t>(stream));
-  return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
-}
-
-extern "C" int attn_probe_matrix_clock(long long* out, int workgroups, int iters, void* stream) {
-  if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 22)) return ATTN_ERR_BAD_ARG;
-  if (!out) return ATTN_ERR_NULL;
-  if (!aligned16(out)) return ATTN_ERR_BAD_ARG;
-  hipError_t e = attn_probe_dispatch(out, workgroups, iters, static_cast<hipStream_t>(stream));
-  return e == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
 }

@@ -1,11 +1,15 @@
-// Measurement aid, not part of the attention path: what the matrix cores of THIS chip sustain.
-// Every wave runs a loop of independent v_mfma_f32_32x32x16_bf16 instructions on register
-// operands (no memory traffic at all); wave 0 of work-group 0 reads the shader-clock counter and
-// the constant-rate (100 MHz) counter around its loop.  Their ratio is the shader clock the chip
-// settles at under sustained matrix load; (instructions issued) x 32768 FLOP / elapsed time is the
-// matrix-instruction ceiling at that clock, against which a kernel's rate can be put next to the
-// nominal peak.
+// Measurement aids for the benchmark, built into a library of their own (libattn_probe_gfx950.so,
+// declared in probe.h): no attention arithmetic, nothing from the paper.
+//
+// Matrix cores: every wave runs a loop of independent v_mfma_f32_32x32x16_bf16 instructions on
+// register operands (no memory traffic at all); the first wave of EVERY work-group reads the
+// shader-clock counter and the constant-rate (100 MHz) counter around its loop and records both.
+// Their ratio is the shader clock that work-group's CU ran at under sustained matrix load; the
+// longest loop in constant-rate ticks is the kernel's duration as the device saw it; (instructions
+// issued) x 32768 FLOP / elapsed time is the matrix-instruction ceiling, against which a kernel's
+// rate can be put next to the nominal peak.
 #include "common.hpp"
+#include "probe.h"
 
 namespace {
 
@@ -33,7 +37,10 @@ __global__ __launch_bounds__(256, 2) void mfma_probe_kernel(long long* __restric
 #pragma unroll
     for (int i = 0; i < 16; ++i) s += acc[j][i];
   if (s == 12345.678f) out[2] = 1;                 // keeps the loop alive; never true
-  if (blockIdx.x == 0 && threadIdx.x == 0) { out[0] = c1 - c0; out[1] = w1 - w0; }
+  if (threadIdx.x == 0) {
+    out[4 + 2 * blockIdx.x] = c1 - c0; out[5 + 2 * blockIdx.x] = w1 - w0;
+    if (blockIdx.x == 0) { out[0] = c1 - c0; out[1] = w1 - w0; }
+  }
 }
 
 // The same for the LDS: four waves per work-group, each issuing 16 * iters conflict-free LDS
@@ -84,13 +91,23 @@ __global__ __launch_bounds__(256, 1) void lds_probe_kernel(long long* __restrict
 
 }  // namespace
 
-hipError_t attn_probe_lds_dispatch(long long* out, int kind, int workgroups, int iters, hipStream_t st) {
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+extern "C" int attn_probe_lds_clock(long long* out, int kind, int workgroups, int iters, void* stream) {
+  if (kind < 0 || kind > 1) return 2;
+  if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 22)) return 2;
+  if (!out) return 1;
+  if (!aligned16(out)) return 2;
+  hipStream_t st = static_cast<hipStream_t>(stream);
   if (kind == 0) hipLaunchKernelGGL(lds_probe_kernel<0>, dim3(workgroups), dim3(256), 0, st, out, iters);
   else hipLaunchKernelGGL(lds_probe_kernel<1>, dim3(workgroups), dim3(256), 0, st, out, iters);
-  return hipGetLastError();
+  return hipGetLastError() == hipSuccess ? 0 : 5;
 }
 
-hipError_t attn_probe_dispatch(long long* out, int workgroups, int iters, hipStream_t st) {
-  hipLaunchKernelGGL(mfma_probe_kernel, dim3(workgroups), dim3(256), 0, st, out, iters);
-  return hipGetLastError();
+extern "C" int attn_probe_matrix_clock(long long* out, int workgroups, int iters, void* stream) {
+  if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 22)) return 2;
+  if (!out) return 1;
+  if (!aligned16(out)) return 2;
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(stream), out, iters);
+  return hipGetLastError() == hipSuccess ? 0 : 5;
 }

@@ -429,12 +429,13 @@ def test_grouped_query_attention(lib, H, Hkv, N, d, causal):
 def test_lds_probe(lib):
     """The LDS read loops report the hardware's rates: one wave-wide read instruction per 4 clocks
     and CU, i.e. 256 bytes per clock for ds_read_b128 and 128 for the transposing 8-byte read."""
-    r = lib.probe_lds_clock(kind=0, workgroups=256, iters=2000)
+    from paper_2510_04212_amd import probe
+    r = probe.lds_clock(kind=0, workgroups=256, iters=2000)
     assert 200.0 < r["bytes_per_clk_per_cu"] <= 257.0, r
     assert 1.0 < r["shader_clock_ghz"] < 2.6, r
-    t = lib.probe_lds_clock(kind=1, workgroups=256, iters=2000)
+    t = probe.lds_clock(kind=1, workgroups=256, iters=2000)
     assert 100.0 < t["bytes_per_clk_per_cu"] <= 129.0, t
-    raw = lib.raw()
+    raw = probe.raw()
     out = torch.zeros(4, dtype=torch.int64, device=DEV)
     assert raw.attn_probe_lds_clock(out.data_ptr(), 0, 0, 10, None) == 2
     assert raw.attn_probe_lds_clock(out.data_ptr(), 2, 8, 10, None) == 2
@@ -443,12 +444,18 @@ def test_lds_probe(lib):
 
 def test_matrix_clock_probe(lib):
     """The benchmark's measurement aid: plausible clock and rate, argument checks."""
-    p = lib.probe_matrix_clock(workgroups=512, iters=2000)
-    print(f"\nprobe: {p['shader_clock_ghz']:.2f} GHz, {p['tflops']:.0f} TFLOP/s over {p['ms']:.2f} ms")
-    assert 0.8 < p["shader_clock_ghz"] < 2.7
+    from paper_2510_04212_amd import probe
+    p = probe.matrix_clock(workgroups=1024, iters=10000)
+    print(f"\nprobe: {p['shader_clock_ghz']:.2f} GHz ({p['shader_clock_ghz_min']:.2f}..{p['shader_clock_ghz_max']:.2f}), "
+          f"{p['tflops']:.0f} TFLOP/s over {p['ms']:.2f} ms (device {p['device_ms']:.2f} ms), {p['clocks_per_mfma']:.1f} clocks per instruction")
+    assert 0.8 < p["shader_clock_ghz_min"] <= p["shader_clock_ghz"] <= p["shader_clock_ghz_max"] < 2.7
     assert 300 < p["tflops"] < 2600
-    out = torch.zeros(4, dtype=torch.int64, device=DEV)
-    raw = lib.raw()
+    # self-consistency: clock x 4096 FLOP/clk/CU x 256 CUs reproduces the rate (8 passes of 4 clocks
+    # per instruction and SIMD)
+    assert 31.0 < p["clocks_per_mfma"] < 36.0
+    assert p["device_ms"] <= p["ms"] * 1.02
+    out = torch.zeros(4 + 2 * 8, dtype=torch.int64, device=DEV)
+    raw = probe.raw()
     assert raw.attn_probe_matrix_clock(out.data_ptr(), 0, 10, None) == 2
     assert raw.attn_probe_matrix_clock(out.data_ptr(), 8, 0, None) == 2
     assert raw.attn_probe_matrix_clock(None, 8, 10, None) == 1

@@ -15,19 +15,33 @@ def binding():
     return b
 
 
-def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "attn.h")).read()
+def _declared_functions(header):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b(attn_[a-z_]+)\s*\(", text)
     return sorted(set(names))
 
 
 def test_every_declared_symbol_is_exported(binding):
-    declared = _declared_functions()
+    declared = _declared_functions(os.path.join(ROOT, "include", "attn.h"))
     assert set(declared) == set(binding.EXPORTS)
     lib = ctypes.CDLL(binding.LIB_PATH)
     for name in declared:
         assert hasattr(lib, name), name
+    assert not any("probe" in n for n in declared)       # measurement aids are not part of the boundary
+
+
+def test_the_probe_library_exports_what_its_header_declares():
+    from paper_2510_04212_amd import probe
+    declared = _declared_functions(os.path.join(ROOT, "paper_2510_04212_amd", "csrc", "probe.h"))
+    assert declared == ["attn_probe_lds_clock", "attn_probe_matrix_clock"]
+    lib = ctypes.CDLL(probe.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    # argument checks happen on the host, before any launch
+    assert lib.attn_probe_matrix_clock(None, 8, 10, None) == 1
+    assert lib.attn_probe_matrix_clock(ctypes.c_void_p(0x1000), 0, 10, None) == 2
+    assert lib.attn_probe_lds_clock(ctypes.c_void_p(0x1000), 2, 8, 10, None) == 2
 
 
 def test_status_strings(binding):
