@@ -183,6 +183,24 @@ int attn_bwd(const void* Q, const void* K, const void* V, const void* O, const v
 size_t attn_bwd_workspace_bytes(int B, int H, int N, int d);
 
 /*
+ * attn_bwd for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * arithmetic, kernels, checks and error codes as attn_bwd, minus the workspace: delta lives in a
+ * 4 MiB device array inside the library (one copy per GPU, held until the process ends).
+ *   - B*H*N must not exceed attn_bwd_noalloc_max_rows() (2^20 rows): ATTN_ERR_WORKSPACE otherwise.
+ *   - The call allocates nothing, frees nothing and does not synchronise.
+ *   - Every call on a GPU uses that GPU's one array: calls that overlap in time on the same GPU
+ *     (different streams, or graphs replayed concurrently) race on it and must be serialised by
+ *     the caller.  Nothing needs to be cleared between calls: every value read is written by the
+ *     same call first.
+ */
+int attn_bwd_noalloc(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                     const float* LSE, void* dQ, void* dK, void* dV,
+                     int B, int H, int N, int d, int causal, float softmax_scale, int variant,
+                     void* stream);
+size_t attn_bwd_noalloc_max_rows(void);
+
+/*
  * The stages of attn_bwd, exposed separately so that a caller can time them or feed them
  * another delta.  attn_bwd == attn_bwd_dq_delta (delta into the workspace), then attn_bwd_dkdv;
  * attn_delta, then attn_bwd_dkdv and attn_bwd_dq in either order, gives the same bits.

@@ -53,6 +53,10 @@ _lib.attn_bwd_rect.argtypes = [_vp] * 9 + [_vp, _sz, _i, _i, _i, _i, _i, _i, _f,
 _lib.attn_bwd_rect.restype = _i
 _lib.attn_bwd.argtypes = [_vp] * 9 + [_vp, _sz, _i, _i, _i, _i, _i, _f, _i, _vp]
 _lib.attn_bwd.restype = _i
+_lib.attn_bwd_noalloc.argtypes = [_vp] * 9 + [_i, _i, _i, _i, _i, _f, _i, _vp]
+_lib.attn_bwd_noalloc.restype = _i
+_lib.attn_bwd_noalloc_max_rows.argtypes = []
+_lib.attn_bwd_noalloc_max_rows.restype = _sz
 _lib.attn_bwd_dkdv.argtypes = [_vp] * 8 + [_i, _i, _i, _i, _i, _f, _vp]
 _lib.attn_bwd_dkdv.restype = _i
 _lib.attn_bwd_dq.argtypes = [_vp] * 7 + [_i, _i, _i, _i, _i, _f, _vp]
@@ -71,7 +75,7 @@ FWD_PV_E4M3 = 2
 FWD_GUARD_UNDERFLOW = 4
 
 EXPORTS = ["attn_fwd", "attn_fwd_ex", "attn_fwd_opt", "attn_delta", "attn_delta_hp",
-           "attn_delta_recompute", "attn_bwd",
+           "attn_delta_recompute", "attn_bwd", "attn_bwd_noalloc", "attn_bwd_noalloc_max_rows",
            "attn_bwd_dkdv", "attn_bwd_dq", "attn_bwd_dq_delta", "attn_fwd_strided", "attn_bwd_strided",
            "attn_fwd_gqa", "attn_bwd_gqa", "attn_fwd_rect", "attn_bwd_rect",
            "attn_bwd_workspace_bytes",
@@ -228,6 +232,19 @@ def attn_bwd(Q, K, V, O, dO, LSE, causal, softmax_scale, variant=STANDARD,
                        _ptr(dV), _ptr(workspace), workspace.numel(), B, H, N, d, int(bool(causal)),
                        float(softmax_scale), int(variant), _stream(stream))
     _check(st)
+    return dQ, dK, dV
+
+
+def attn_bwd_noalloc(Q, K, V, O, dO, LSE, causal, softmax_scale, dQ, dK, dV, variant=STANDARD, stream=None):
+    """attn_bwd_noalloc of the C ABI: attn_bwd with delta in the library's own device array.  The
+    outputs are the caller's (this wrapper allocates nothing either)."""
+    B, H, N, d = _bhnd(Q, "Q")
+    for n, t in (("K", K), ("V", V), ("O", O), ("dO", dO), ("dQ", dQ), ("dK", dK), ("dV", dV)):
+        if _bhnd(t, n) != (B, H, N, d):
+            raise ValueError(f"{n} shape differs from Q")
+    _check(_lib.attn_bwd_noalloc(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK),
+                                 _ptr(dV), B, H, N, d, int(bool(causal)), float(softmax_scale), int(variant),
+                                 _stream(stream)))
     return dQ, dK, dV
 
 

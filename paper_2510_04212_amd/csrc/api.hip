@@ -1,6 +1,7 @@
 // C ABI of the attention library (see include/attn.h): argument validation and dispatch only.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include <cmath>
 #include "../../include/attn.h"
 
@@ -71,7 +72,7 @@ extern "C" const char* attn_status_string(int status) {
     case ATTN_ERR_NULL: return "ATTN_ERR_NULL: a required pointer is NULL";
     case ATTN_ERR_BAD_ARG: return "ATTN_ERR_BAD_ARG: invalid argument value or misaligned pointer";
     case ATTN_ERR_UNSUPPORTED: return "ATTN_ERR_UNSUPPORTED: d must be 32, 64, 96, 128 or 256 and N positive";
-    case ATTN_ERR_WORKSPACE: return "ATTN_ERR_WORKSPACE: workspace too small or misaligned";
+    case ATTN_ERR_WORKSPACE: return "ATTN_ERR_WORKSPACE: workspace too small or misaligned (attn_bwd_noalloc: B*H*N above attn_bwd_noalloc_max_rows())";
     case ATTN_ERR_LAUNCH: return "ATTN_ERR_LAUNCH: HIP launch failed";
     default: return "unknown attn_status";
   }
@@ -284,6 +285,49 @@ extern "C" int attn_bwd(const void* Q, const void* K, const void* V, const void*
                         float softmax_scale, int variant, void* stream) {
   return bwd_entry(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, H, N, d, causal,
                    softmax_scale, variant, nullptr, stream);
+}
+
+// ---- attn_bwd for callers that cannot allocate.  delta, the one buffer attn_bwd takes through its
+// workspace argument, lives in a device array of this library instead: one copy per GPU, at an
+// address of its own on each, held until the process ends.
+constexpr size_t kScratchRows = (size_t)1 << 20;                  // B*H*N at most; 4 MiB of float32
+static __device__ __align__(256) float scratch[kScratchRows];
+constexpr int kMaxDevices = 64;
+static std::atomic<float*> scratch_ptr[kMaxDevices];             // device address of `scratch`, per GPU
+
+// Device address of this GPU's copy of `scratch` (looked up once per device, with that device
+// current; in host code the array's name is only a handle for this lookup).
+static int scratch_address(float** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ATTN_ERR_LAUNCH;
+  float* p = scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    void* sym = nullptr;
+    if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || sym == nullptr) return ATTN_ERR_LAUNCH;
+    p = static_cast<float*>(sym);
+    scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return ATTN_OK;
+}
+
+extern "C" size_t attn_bwd_noalloc_max_rows(void) { return kScratchRows; }
+
+extern "C" int attn_bwd_noalloc(const void* Q, const void* K, const void* V, const void* O,
+                                const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
+                                int B, int H, int N, int d, int causal, float softmax_scale,
+                                int variant, void* stream) {
+  bool empty;
+  int st = check_shape(B, H, N, d, &empty);
+  if (st != ATTN_OK) return st;
+  if (!empty && (size_t)B * H * (size_t)N > kScratchRows) return ATTN_ERR_WORKSPACE;
+  float* delta = nullptr;
+  if (!empty && (st = scratch_address(&delta)) != ATTN_OK) return st;
+  // every row of delta that the dK/dV kernel reads is written by the dQ kernel first: nothing
+  // needs clearing between calls
+  return bwd_entry(Q, K, V, O, dO, LSE, dQ, dK, dV, empty ? nullptr : delta,
+                   kScratchRows * sizeof(float), B, H, N, d, causal, softmax_scale, variant, nullptr,
+                   stream);
 }
 
 extern "C" int attn_bwd_strided(const void* Q, const void* K, const void* V, const void* O,
