@@ -50,6 +50,8 @@ def matrix_clock(workgroups=512, iters=50000, stream=None):
     out = torch.zeros(4 + 2 * workgroups, dtype=torch.int64, device="cuda")
     e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
     s = torch.cuda.current_stream() if stream is None else stream
+    # a first, tiny launch: loading the kernel's code must not fall between the two events
+    _check(_lib.attn_probe_matrix_clock(ctypes.c_void_p(out.data_ptr()), 1, 1, _stream(stream)))
     e0.record(s)
     _check(_lib.attn_probe_matrix_clock(ctypes.c_void_p(out.data_ptr()), int(workgroups), int(iters), _stream(stream)))
     e1.record(s)
@@ -74,6 +76,7 @@ def lds_clock(kind=0, workgroups=256, iters=20000, stream=None):
     out = torch.zeros(4, dtype=torch.int64, device="cuda")
     e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
     s = torch.cuda.current_stream() if stream is None else stream
+    _check(_lib.attn_probe_lds_clock(ctypes.c_void_p(out.data_ptr()), int(kind), 1, 1, _stream(stream)))
     e0.record(s)
     _check(_lib.attn_probe_lds_clock(ctypes.c_void_p(out.data_ptr()), int(kind), int(workgroups), int(iters), _stream(stream)))
     e1.record(s)
