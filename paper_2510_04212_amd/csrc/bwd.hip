@@ -404,7 +404,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const bf16_t* __restrict__ O, bf16_t* __restrict__ dQ, float* __restrict__ delta_out, int N,
-    float alpha, Layout lay) {
+    float alpha, Layout lay, int pairs) {
   constexpr bool DELTA_MODE = MODE == kRecomputeDelta;
   constexpr int TILE_BYTES = kKTile * kLdsD<D> * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -419,15 +419,27 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
   const int NK = RAGGED ? lay.Nk : N;                 // bounds-checking instantiation: N queries, NK keys,
   const int shift = RAGGED ? NK - N : 0;              // causal mask  key <= query + shift
   const int nqt = (N + kQPerWG - 1) / kQPerWG;
+  // pairs != 0 (causal problems with enough work-groups): a work-group takes query block
+  // nqt-1-idx and then its mirror image idx; together they always meet the same number of key
+  // tiles, so every work-group carries the same load and the grid has no tail of heavy blocks.
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
-  const int bh = wg / nqt;
-  const int qt = nqt - 1 - (wg % nqt + (CAUSAL ? small_grid_rotation(bh, nqt, gridDim.x, D == 128 ? 768 : 1152) : 0)) % nqt;
-  const int q0 = qt * kQPerWG;
-  const int qw = q0 + 32 * wave;
+  const int npw = pairs ? (nqt + 1) / 2 : nqt;          // work-groups per head
+  const int bh = wg / npw;
+  const int idx = wg % npw;
   const size_t head_off = head_base(lay, bh);
   const int sn = lay.sn;
   const bf16_t* Kh = K + head_base_kv(lay, bh);
   const bf16_t* Vh = V + head_base_kv(lay, bh);
+  const float c2 = alpha * kLog2e;
+  TileLoader<D> loader;
+  loader.init(tid, sn);
+
+  for (int part = 0; part < (pairs ? 2 : 1); ++part) {
+  const int qt = pairs ? (part == 0 ? nqt - 1 - idx : idx)
+                       : nqt - 1 - (idx + (CAUSAL ? small_grid_rotation(bh, nqt, gridDim.x, D == 128 ? 768 : 1152) : 0)) % nqt;
+  if (part == 1 && qt == nqt - 1 - idx) break;        // odd number of blocks: the middle one has no partner
+  const int q0 = qt * kQPerWG;
+  const int qw = q0 + 32 * wave;
 
   // Q_i^T / dO_i^T fragments (B operands): lane (r,h) holds Q[qw + r][16kc + 8h .. +7]
   // (rows past the sequence end read the last row; their dQ is not stored)
@@ -481,10 +493,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
 
   const int kend = !CAUSAL ? NK : !RAGGED ? q0 + kQPerWG : max(0, min(NK, q0 + kQPerWG + shift));
   const int ntiles = RAGGED ? (kend + kKTile - 1) / kKTile : kend / kKTile;
-  const float c2 = alpha * kLog2e;
 
-  TileLoader<D> loader;
-  loader.init(tid, sn);
   loader.template load_rows<RAGGED>(ldsK, Kh, 0, NK, tid);
   loader.template load_rows<RAGGED>(ldsV, Vh, 0, NK, tid);
   wait_vmem();
@@ -562,9 +571,10 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
   if (DELTA_MODE) {
     const float dsum = sum_with_partner32(pdp);      // the partner lane holds the other keys of every block
     if (h == 0 && (!RAGGED || qw + r < N)) delta_out[(size_t)bh * N + qw + r] = dsum;
-    return;
+    continue;
   }
   if (!RAGGED || qw + r < N) store_acc_T<D / 32>(dQ + head_off + (size_t)(qw + r) * sn, dQt, alpha, h);
+  }   // part
 }
 
 template <typename KernT>
@@ -601,9 +611,13 @@ static hipError_t launch_dq(const void* Q, const void* K, const void* V, const v
   auto k = attn_bwd_dq_kernel<D, CAUSAL, RAGGED, MODE>;
   hipError_t e;
   if ((e = set_smem(k, smem, set)) != hipSuccess) return e;
-  hipLaunchKernelGGL(k, dim3(BH * ((N + kQPerWG - 1) / kQPerWG)), dim3(256), smem, st, (const bf16_t*)Q,
+  // as in the forward: mirrored pairs of query blocks under the causal mask when that still
+  // leaves at least two full rounds of work-groups
+  const int nqt = (N + kQPerWG - 1) / kQPerWG;
+  const int pairs = (CAUSAL && (long long)BH * ((nqt + 1) / 2) >= 1024) ? 1 : 0;
+  hipLaunchKernelGGL(k, dim3(BH * (pairs ? (nqt + 1) / 2 : nqt)), dim3(256), smem, st, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
-                     (const bf16_t*)O, (bf16_t*)dQ, delta_out, N, alpha, lay);
+                     (const bf16_t*)O, (bf16_t*)dQ, delta_out, N, alpha, lay, pairs);
   return hipGetLastError();
 }
 

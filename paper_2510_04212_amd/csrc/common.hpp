@@ -303,6 +303,25 @@ DEVI float add_pair_bf16(bf16x2 p, float acc) {
   return __builtin_amdgcn_fdot2_f32_bf16(p, one, acc, false);
 }
 
+// x / l for the many x that share one divisor l (a row's outputs): a reciprocal of l refined by
+// one Newton step, then per quotient one product and one residual correction.  The result is the
+// correctly rounded quotient up to rare last-bit cases, and exact whenever l is a power of two;
+// 4 instructions per quotient instead of the ~10 of a full division.  A subnormal or tiny l (the
+// reciprocal instruction takes no subnormal inputs) is handled by scaling numerator and
+// denominator by 2^64 first, which is exact.  l = 0 gives NaN.
+struct Divisor { float l, r, scale; };
+DEVI Divisor make_divisor(float l) {
+  const float scale = l < 0x1p-64f ? 0x1p64f : 1.0f;
+  const float ls = l * scale;
+  const float r0 = __builtin_amdgcn_rcpf(ls);
+  return Divisor{ls, __builtin_fmaf(__builtin_fmaf(-ls, r0, 1.0f), r0, r0), scale};
+}
+DEVI float divide(float x, Divisor d) {
+  const float xs = x * d.scale;
+  const float q = xs * d.r;
+  return __builtin_fmaf(__builtin_fmaf(-q, d.l, xs), d.r, q);
+}
+
 // Issue-order hints for one scheduling region (basic block) that holds N matrix instructions,
 // each fed by PER LDS fragment reads: the reads are issued AHEAD matrix instructions before
 // their use, so that LDS latency is covered by matrix-core work instead of stalling the wave.

@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256)
 __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 128 ? 1 : 8)))) void attn_fwd_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, float* __restrict__ LSE, int N, float alpha, float beta, float eps,
-    FwdExtras ex, Layout lay) {
+    FwdExtras ex, Layout lay, int pairs) {
   constexpr int TILE_BYTES = kBc * kLdsD<D> * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   // layout: K buffers [2][TILE_BYTES], then V buffers [2][TILE_BYTES]
@@ -84,14 +84,14 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
   const int NK = RAGGED ? lay.Nk : N;
   const int shift = RAGGED ? NK - N : 0;
   const int nqt = (N + kBr - 1) / kBr;
+  // pairs != 0 (causal problems with enough work-groups): a work-group takes query block
+  // nqt-1-idx and then its mirror image idx, which together always meet the same number of key
+  // tiles, so every work-group carries the same load, there is no tail of heavy blocks at the
+  // end of the grid, and half as many work-groups have to start and drain.
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
-  const int bh = wg / nqt;
-  // heavy (late) query blocks first under the causal mask
-  const int qt = nqt - 1 - (wg % nqt + (CAUSAL ? small_grid_rotation(bh, nqt, gridDim.x, D == 128 ? 768 : 1536) : 0)) % nqt;
-  const int q0 = qt * kBr;
-  const int qw = q0 + 32 * wave;                 // first query row of this wave
-  const int q = qw + r;
-  const int qc = (RAGGED && q >= N) ? N - 1 : q;   // row actually read for this lane
+  const int npw = pairs ? (nqt + 1) / 2 : nqt;          // work-groups per head
+  const int bh = wg / npw;
+  const int idx = wg % npw;
   const size_t head_off = head_base(lay, bh);
   const int sn = lay.sn;
   const bf16_t* Qh = Q + head_off;
@@ -103,6 +103,19 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
   FragOffsets<D> fo;
   init_frag_offsets<D>(fo, lane);
   frag_offsets_add_base<D>(fo, lds_address(smem));
+  const float c2 = alpha * kLog2e;
+  // Alg. 3's test  r_m - alpha*s <= eps  in terms of the raw score s:  s >= (r_m - eps) / alpha
+  const float inv_alpha = 1.0f / alpha;
+
+  for (int part = 0; part < (pairs ? 2 : 1); ++part) {
+  // heavy (late) query blocks first under the causal mask
+  const int qt = pairs ? (part == 0 ? nqt - 1 - idx : idx)
+                       : nqt - 1 - (idx + (CAUSAL ? small_grid_rotation(bh, nqt, gridDim.x, D == 128 ? 768 : 1536) : 0)) % nqt;
+  if (part == 1 && qt == nqt - 1 - idx) break;        // odd number of blocks: the middle one has no partner
+  const int q0 = qt * kBr;
+  const int qw = q0 + 32 * wave;                 // first query row of this wave
+  const int q = qw + r;
+  const int qc = (RAGGED && q >= N) ? N - 1 : q;   // row actually read for this lane
 
   // keys [0, kend) can matter to this block
   const int kend = !CAUSAL ? NK : !RAGGED ? q0 + kBr : max(0, min(NK, q0 + kBr + shift));
@@ -128,9 +141,6 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
   // normaliser chosen by the kRowStats pass)
   float m = (VARIANT == kFixedNorm) ? LSE[(size_t)bh * N + qc] : -INFINITY;
   float lsum = 0.f;         // this lane's share of the running row sum (its 32 of the 64 keys per tile)
-  const float c2 = alpha * kLog2e;
-  // Alg. 3's test  r_m - alpha*s <= eps  in terms of the raw score s:  s >= (r_m - eps) / alpha
-  const float inv_alpha = 1.0f / alpha;
 
   wait_vmem();
 #pragma unroll
@@ -355,7 +365,7 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
       LSE[(size_t)bh * N + q] = m_row;
       if (EXTRAS && ex.fired != nullptr) ex.fired[(size_t)bh * N + q] = (m_row != r_m) ? 1 : 0;
     }
-    return;
+    continue;
   }
   // ---- epilogue (Alg. 1 steps 10-13).  Rounding points of Sec. 3.3.2: the unnormalised
   // output is rounded to bf16 first, then divided by l, then rounded again.
@@ -365,10 +375,11 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
     auto sw = __builtin_amdgcn_permlane32_swap((unsigned)ones_cnt, (unsigned)ones_cnt, false, false);
     ones_row = (int)(sw[0] + sw[1]);
   }
-  if (RAGGED && q >= N) return;                            // rows past the sequence end exist only as padding
+  if (!RAGGED || q < N) {                                  // rows past the sequence end exist only as padding
   bf16_t* Oq = O + head_off + (size_t)q * sn;
   const bool keep_obar_f32 = EXTRAS && ex.single_rounding != 0;
   const bool unseen_row = RAGGED && m == -INFINITY;        // no visible key (more queries than keys): O = 0, LSE = -inf
+  const Divisor by_l = make_divisor(l);
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -378,13 +389,13 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
       for (int e = 0; e < 4; ++e) {
         const float a = acc[db][4 * g + e];
         const float obar = keep_obar_f32 ? a : (float)(bf16_t)a;
-        o4[e] = (bf16_t)(unseen_row ? 0.f : obar / l);
+        o4[e] = (bf16_t)(unseen_row ? 0.f : divide(obar, by_l));
       }
       *reinterpret_cast<bf16x4*>(Oq + 32 * db + 8 * g + 4 * h) = o4;
       if (EXTRAS && ex.O_hp != nullptr) {
         f32x4 hp;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) hp[e] = unseen_row ? 0.f : acc[db][4 * g + e] / l;
+        for (int e = 0; e < 4; ++e) hp[e] = unseen_row ? 0.f : divide(acc[db][4 * g + e], by_l);
         *reinterpret_cast<f32x4*>(ex.O_hp + ((size_t)bh * N + q) * D + 32 * db + 8 * g + 4 * h) = hp;
       }
     }
@@ -393,6 +404,8 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
     if (EXTRAS && ex.ones != nullptr) ex.ones[(size_t)bh * N + q] = ones_row;
     if (EXTRAS && VARIANT != kFixedNorm && ex.fired != nullptr) ex.fired[(size_t)bh * N + q] = fired_cnt;
   }
+  }
+  }   // part
 }
 
 }  // namespace
@@ -412,9 +425,14 @@ static hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* 
     if (e != hipSuccess) return e;
     attr_set.store(true, std::memory_order_release);
   }
-  dim3 grid(BH * ((N + kBr - 1) / kBr));
+  // Under the causal mask a work-group takes a query block and its mirror image (equal work for
+  // all) when that still leaves at least two full rounds of work-groups (two fit a CU, 256 CUs);
+  // smaller grids keep one block per work-group.
+  const int nqt = (N + kBr - 1) / kBr;
+  const int pairs = (CAUSAL && (long long)BH * ((nqt + 1) / 2) >= 1024) ? 1 : 0;
+  dim3 grid(BH * (pairs ? (nqt + 1) / 2 : nqt));
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, (const bf16_t*)Q, (const bf16_t*)K,
-                     (const bf16_t*)V, (bf16_t*)O, LSE, N, alpha, beta, eps, ex, lay);
+                     (const bf16_t*)V, (bf16_t*)O, LSE, N, alpha, beta, eps, ex, lay, pairs);
   return hipGetLastError();
 }
 
