@@ -433,6 +433,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
   const float c2 = alpha * kLog2e;
   TileLoader<D> loader;
   loader.init(tid, sn);
+  FragOffsets<D> fo;
+  init_frag_offsets<D>(fo, lane);
+  frag_offsets_add_base<D>(fo, lds_address(smem));
 
   for (int part = 0; part < (pairs ? 2 : 1); ++part) {
   const int qt = pairs ? (part == 0 ? nqt - 1 - idx : idx)
@@ -480,7 +483,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
   float pdp = 0.f;                                   // DELTA_MODE: this lane's share of sum_k P dP
   // -delta_i in all 16 accumulator slots of the lane: the third operand of the first dP^T matrix
   // instruction of every key block, which then delivers dP - delta with no vector instruction
-  // (Alg. 2 step 12).  Kept opaque so that it stays resident instead of being rebuilt per block.
+  // (Alg. 2: dS = P o (dP - delta)).  Kept opaque so that it stays resident instead of being
+  // rebuilt per block.
   f32x16 neg_delta;
 #pragma unroll
   for (int i = 0; i < 16; ++i) neg_delta[i] = -dl;
@@ -502,10 +506,12 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
   settle(l2);
   __syncthreads();
 
-  for (int j = 0; j < ntiles; ++j) {
-    const int buf = j & 1;
-    const char* tK = smem + buf * TILE_BYTES;
-    const char* tV = smem + (2 + buf) * TILE_BYTES;
+  // One key tile; BUF (which LDS buffer holds it) is a compile-time constant so that every LDS
+  // address is a precomputed per-lane offset plus an immediate.
+  auto tile_step = [&](auto buf_c, int j) {
+    constexpr int buf = decltype(buf_c)::value;
+    constexpr int tK = buf * TILE_BYTES;            // byte offsets of this tile's K and V in smem
+    constexpr int tV = (2 + buf) * TILE_BYTES;
     const bool has_next = (j + 1 < ntiles);
     if (has_next) {
       loader.template load_rows<RAGGED>(smem + (buf ^ 1) * TILE_BYTES, Kh, (j + 1) * kKTile, NK, tid);
@@ -513,35 +519,35 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
     }
     const int kt0 = j * kKTile;
     if (!CAUSAL || (kt0 <= qw + shift + 31)) {
-      auto kblock = [&](auto diag_c, int kb) {
-        constexpr bool DIAG = decltype(diag_c)::value;
+      // one 32-key block against this wave's 32 queries (one code path: the block that crosses the
+      // diagonal only adds a masking step, so that the fragment reads stay next to their matrix
+      // instructions instead of being merged in front of a branch)
+      auto kblock = [&](int kb) {
         const int kb0 = kt0 + 32 * kb;
-        const bool tail = RAGGED && kb0 + 32 > NK;           // some keys lie past the sequence end
         // ---- S^T = K_j Q_i^T, dP^T = V_j dO_i^T ; rows = keys, lane = query
         f32x16 s, dp;
 #pragma unroll
         for (int i = 0; i < 16; ++i) s[i] = 0.f;
 #pragma unroll
         for (int kc = 0; kc < D / 16; ++kc) {
-          s = mfma32(lds_read_row8<D>(tK, 32 * kb + r, 16 * kc + 8 * h), qf[kc], s);
-          dp = mfma32(lds_read_row8<D>(tV, 32 * kb + r, 16 * kc + 8 * h), dof[kc], kc == 0 ? neg_delta : dp);
+          s = mfma32(lds_row8<D>(tK, fo, 32 * kb, kc), qf[kc], s);
+          dp = mfma32(lds_row8<D>(tV, fo, 32 * kb, kc), dof[kc], kc == 0 ? neg_delta : dp);
         }
         sched_reads_ahead_of_mfma<D / 8, 1, 4>();
-        // element i of this lane is key kb0 + 4h + c with c = 8 (i / 4) + i % 4 a compile-time constant
-        if (tail) {   // keys past the sequence end: P = exp(-inf) = 0, so they add nothing to dQ
-          const int lim = NK - kb0 - 4 * h;
+        // element i of this lane is key kb0 + 4h + c with c = 8 (i / 4) + i % 4 a compile-time
+        // constant.  Keys in this lane's future (the block crosses the diagonal) and keys past the
+        // sequence end get S = -inf: P = exp(-inf) = 0, so they add nothing to dQ.
+        if ((CAUSAL && kb0 + 31 > qw + shift) || (RAGGED && kb0 + 32 > NK)) {
+          int lim = CAUSAL ? qw + r + shift - kb0 - 4 * h : 0x7fffffff;     // last visible c
+          if (RAGGED) lim = min(lim, NK - 1 - kb0 - 4 * h);
 #pragma unroll
           for (int i = 0; i < 16; ++i)
-            if (8 * (i >> 2) + (i & 3) >= lim) s[i] = -INFINITY;
+            if (8 * (i >> 2) + (i & 3) > lim) s[i] = -INFINITY;
         }
         bf16x8 dsf[2];
-        const int last_seen = qw + r + shift - kb0 - 4 * h;   // DIAG: keys with c above it lie in this lane's future
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l2));
-          if (DIAG) {
-            if (8 * (i >> 2) + (i & 3) > last_seen) p = 0.f;
-          }
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l2));
           if (DELTA_MODE) pdp = __builtin_fmaf(p, dp[i], pdp);
           else dsf[i >> 3][i & 7] = (bf16_t)(p * dp[i]);      // dp already holds dP - delta
         }
@@ -551,7 +557,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
           for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
             for (int db = 0; db < D / 32; ++db) {
-              dQt[db] = mfma32(lds_read_col8<D>(tK, 32 * kb + 16 * cc, 32 * db, lane), dsf[cc], dQt[db]);
+              dQt[db] = mfma32(lds_col8<D>(tK, fo, 32 * kb + 16 * cc, db), dsf[cc], dQt[db]);
             }
           sched_reads_ahead_of_mfma<D / 16, 2, 4>();
         }
@@ -561,12 +567,15 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
         const int kb0 = kt0 + 32 * kb;
         if (CAUSAL && (kb0 > qw + shift + 31)) continue;   // no query of the wave sees a key of the block
         if (RAGGED && kb0 >= NK) continue;                   // nothing but padding
-        if (CAUSAL && (kb0 + 31 > qw + shift)) kblock(std::true_type{}, kb);
-        else kblock(std::false_type{}, kb);
+        kblock(kb);
       }
     }
     wait_vmem();
     __syncthreads();
+  };
+  for (int j = 0; j < ntiles; j += 2) {
+    tile_step(std::integral_constant<int, 0>{}, j);
+    if (j + 1 < ntiles) tile_step(std::integral_constant<int, 1>{}, j + 1);
   }
   if (DELTA_MODE) {
     const float dsum = sum_with_partner32(pdp);      // the partner lane holds the other keys of every block
