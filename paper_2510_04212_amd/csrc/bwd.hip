@@ -156,9 +156,7 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
     const float* Lh = LSE + (size_t)bq0 * N;
     const float* Dh = delta + (size_t)bq0 * N;
     const int total = group * (nt - t0);
-    auto load_tile = [&](const bf16_t* Qp, const bf16_t* dOp, const float* Lp, const float* Dp, int t, int buf) {
-      loader.template load_rows<RAGGED>(ldsQ + buf * TILE_BYTES, Qp, t * kQTile, N, tid);
-      loader.template load_rows<RAGGED>(ldsdO + buf * TILE_BYTES, dOp, t * kQTile, N, tid);
+    auto load_stats = [&](const float* Lp, const float* Dp, int t) {
       const int row = t * kQTile + (tid & (kQTile - 1));
       const int rowc = (RAGGED && row >= N) ? N - 1 : row;
       if (tid < kQTile) {
@@ -175,7 +173,9 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
         ldsL[buf * kQTile + tid] = l;
       } else if (tid < 2 * kQTile) ldsD[buf * kQTile + tid - kQTile] = -sreg;   // LDS holds -delta
     };
-    load_tile(Qh, dOh, Lh, Dh, t0, 0);
+    loader.template load_rows<RAGGED>(ldsQ, Qh, t0 * kQTile, N, tid);
+    loader.template load_rows<RAGGED>(ldsdO, dOh, t0 * kQTile, N, tid);
+    load_stats(Lh, Dh, t0);
     store_stats(0);
     wait_vmem();
     __syncthreads();
@@ -185,14 +185,22 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
     auto tile_step = [&](auto buf_c, int t, int step) {
       constexpr int buf = decltype(buf_c)::value;
       const bool has_next = (step + 1 < total);
-      if (has_next) {
-        if (GROUPED && t + 1 == nt) {   // on to the next query head of the group
-          Qh += lay.sh; dOh += lay.sh; Lh += N; Dh += N;
-          load_tile(Qh, dOh, Lh, Dh, t0, buf ^ 1);
-        } else {
-          load_tile(Qh, dOh, Lh, Dh, t + 1, buf ^ 1);
-        }
+      // The next tile (after the last one: this tile once more, harmlessly) goes into the other
+      // buffer.  On the pipelined path its transfer instructions are issued one per two slots of
+      // the first phase instead of in one burst behind the barrier.
+      int tn = has_next ? t + 1 : t;
+      if (GROUPED && has_next && t + 1 == nt) {   // on to the next query head of the group
+        Qh += lay.sh; dOh += lay.sh; Lh += N; Dh += N;
+        tn = t0;
       }
+      constexpr int NLD = TileLoader<D>::NI;
+      const auto pendQ = loader.template prepare<RAGGED>(ldsQ + (buf ^ 1) * TILE_BYTES, Qh, tn * kQTile, N);
+      const auto pendD = loader.template prepare<RAGGED>(ldsdO + (buf ^ 1) * TILE_BYTES, dOh, tn * kQTile, N);
+      auto issue_part = [&](int i) {
+        if (i < NLD) loader.template issue<RAGGED>(pendQ, tid, i);
+        else if (i < 2 * NLD) loader.template issue<RAGGED>(pendD, tid, i - NLD);
+      };
+      if (has_next) load_stats(Lh, Dh, tn);
       constexpr int tQ = buf * TILE_BYTES;          // byte offsets of this tile's Q and dO in smem
       constexpr int tdO = (2 + buf) * TILE_BYTES;
       const float* tL = reinterpret_cast<const float*>(smem + 4 * TILE_BYTES) + buf * kQTile;
@@ -300,8 +308,11 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
           ring[(sl + AH) % R] = (sl + AH < NS) ? rd_sdp(0, sl + AH) : rd_sdp(1, sl + AH - NS);
           if (sl & 1) dp0 = mfma32(ring[sl % R], vf[sl >> 1], dp0);
           else s0 = mfma32(ring[sl % R], kf[sl >> 1], s0);
+          if (sl & 1) issue_part(sl >> 1);
           __builtin_amdgcn_sched_barrier(0);
         }
+#pragma unroll
+        for (int i = NS / 2; i < 2 * NLD; ++i) issue_part(i);
 #pragma unroll
         for (int g = 0; g < 4; ++g) lq1[g] = *reinterpret_cast<const f32x4*>(tL + 32 + 8 * g + 4 * h);
         // ---- phase 2
@@ -350,6 +361,8 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
       if (DS == 1 && D != 96 && (!CAUSAL || qt0 + shift >= kw + 31) && (!RAGGED || qt0 + kQTile <= N)) {
         tile_pipelined();
       } else {
+#pragma unroll
+        for (int i = 0; i < 2 * NLD; ++i) issue_part(i);
 #pragma unroll
         for (int qb = 0; qb < kQTile / 32; ++qb) {
           const int qb0 = qt0 + 32 * qb;
@@ -512,17 +525,26 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
     constexpr int buf = decltype(buf_c)::value;
     constexpr int tK = buf * TILE_BYTES;            // byte offsets of this tile's K and V in smem
     constexpr int tV = (2 + buf) * TILE_BYTES;
-    const bool has_next = (j + 1 < ntiles);
-    if (has_next) {
-      loader.template load_rows<RAGGED>(smem + (buf ^ 1) * TILE_BYTES, Kh, (j + 1) * kKTile, NK, tid);
-      loader.template load_rows<RAGGED>(smem + (2 + (buf ^ 1)) * TILE_BYTES, Vh, (j + 1) * kKTile, NK, tid);
-    }
+    // The next tile lands in the other buffer while this one is being processed; its transfer
+    // instructions are issued one per step of the first block's score products rather than in one
+    // burst behind the barrier.  After the last tile the current one is fetched once more into the
+    // idle buffer (harmless; keeps the instruction stream free of branches).
+    const int jn = (j + 1 < ntiles) ? j + 1 : j;
+    constexpr int NLD = TileLoader<D>::NI;
+    const auto pendK = loader.template prepare<RAGGED>(smem + (buf ^ 1) * TILE_BYTES, Kh, jn * kKTile, NK);
+    const auto pendV = loader.template prepare<RAGGED>(smem + (2 + (buf ^ 1)) * TILE_BYTES, Vh, jn * kKTile, NK);
+    auto issue_part = [&](int i) {
+      if (i < NLD) loader.template issue<RAGGED>(pendK, tid, i);
+      else if (i < 2 * NLD) loader.template issue<RAGGED>(pendV, tid, i - NLD);
+    };
+    bool issued = false;
     const int kt0 = j * kKTile;
     if (!CAUSAL || (kt0 <= qw + shift + 31)) {
       // one 32-key block against this wave's 32 queries (one code path: the block that crosses the
       // diagonal only adds a masking step, so that the fragment reads stay next to their matrix
       // instructions instead of being merged in front of a branch)
-      auto kblock = [&](int kb) {
+      auto kblock = [&](int kb, auto first_c) {
+        constexpr bool first = decltype(first_c)::value;     // the block that also issues the tile transfer
         const int kb0 = kt0 + 32 * kb;
         // ---- S^T = K_j Q_i^T, dP^T = V_j dO_i^T ; rows = keys, lane = query
         f32x16 s, dp;
@@ -532,6 +554,12 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
         for (int kc = 0; kc < D / 16; ++kc) {
           s = mfma32(lds_row8<D>(tK, fo, 32 * kb, kc), qf[kc], s);
           dp = mfma32(lds_row8<D>(tV, fo, 32 * kb, kc), dof[kc], kc == 0 ? neg_delta : dp);
+          if (first) issue_part(kc);
+        }
+        if (first) {
+#pragma unroll
+          for (int i = D / 16; i < 2 * NLD; ++i) issue_part(i);
+          issued = true;
         }
         sched_reads_ahead_of_mfma<D / 8, 1, 4>();
         // element i of this lane is key kb0 + 4h + c with c = 8 (i / 4) + i % 4 a compile-time
@@ -567,8 +595,13 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
         const int kb0 = kt0 + 32 * kb;
         if (CAUSAL && (kb0 > qw + shift + 31)) continue;   // no query of the wave sees a key of the block
         if (RAGGED && kb0 >= NK) continue;                   // nothing but padding
-        kblock(kb);
+        if (kb == 0) kblock(kb, std::true_type{});
+        else kblock(kb, std::false_type{});
       }
+    }
+    if (!issued) {      // a wave that skipped the tile's first block still has its share of the transfer to issue
+#pragma unroll
+      for (int i = 0; i < 2 * NLD; ++i) issue_part(i);
     }
     wait_vmem();
     __syncthreads();

@@ -269,6 +269,34 @@ template <int D> struct TileLoader {
     if (!RAGGED || row0 + 64 <= N) load(tile, src);
     else load_clamped(tile, src, N - row0, tid);
   }
+  // A tile transfer prepared once (scalar operands) and issued one instruction at a time, so that a
+  // caller can spread it over its matrix instructions instead of issuing it in one burst.
+  struct Pending { const bf16_t* src; unsigned base; int valid; };
+  template <bool RAGGED>
+  DEVI Pending prepare(const char* tile, const bf16_t* tensor, int row0, int N) const {
+    typedef __attribute__((address_space(3))) const char lds_char;
+    Pending p;
+    p.src = wave_uniform(tensor + (size_t)row0 * sn);
+    p.base = __builtin_amdgcn_readfirstlane((unsigned)(unsigned long)((lds_char*)tile) + lds_wave);
+    p.valid = RAGGED ? N - row0 : 64;
+    return p;
+  }
+  // instruction i (0 .. NI-1) of the prepared transfer
+  template <bool RAGGED>
+  DEVI void issue(const Pending& p, int tid, int i) const {
+    unsigned vo = voff[i];
+    if (RAGGED && p.valid < 64) {
+      const int wave = tid >> 6, lane = tid & 63;
+      const int row = (wave * NI + i) * RPI + lane / CH;
+      const int c = src_chunk(lane % CH, row);
+      const int rc = row < p.valid ? row : p.valid - 1;
+      vo = (unsigned)(rc * sn + c * 8) * 2u;
+    }
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(p.base + (unsigned)(i * RPI * DL * 2)), "v"(vo), "s"(p.src)
+                 : "m0");
+  }
   // tile: LDS address of the destination tile; src: first row of the 64-row source tile (wave-uniform)
   DEVI void load(const char* tile, const bf16_t* src) const {
     typedef __attribute__((address_space(3))) const char lds_char;

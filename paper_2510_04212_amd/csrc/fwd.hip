@@ -154,11 +154,21 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
     constexpr int BUF = decltype(buf_c)::value;
     constexpr int tK = BUF * TILE_BYTES;          // byte offsets of this tile's K and V in smem
     constexpr int tV = (2 + BUF) * TILE_BYTES;
-    if (j + 1 < ntiles) {   // lands in the other buffer while this tile is being processed
-      loader.template load_rows<RAGGED>(smem + (BUF ^ 1) * TILE_BYTES, Kh, (j + 1) * kBc, NK, tid);
-      if (VARIANT != kRowStats)
-        loader.template load_rows<RAGGED>(smem + (2 + (BUF ^ 1)) * TILE_BYTES, Vh, (j + 1) * kBc, NK, tid);
-    }
+    // The next tile lands in the other buffer while this one is being processed.  Its transfer
+    // instructions are not issued in one burst (all eight waves of a CU would queue 64 KB of
+    // requests right behind the barrier and sit at the head of the tile until the queue takes
+    // them) but one per step of the score product.  After the last tile the current one is
+    // fetched once more into the idle buffer: harmless, and the instruction stream stays free of
+    // branches.
+    const int jn = (j + 1 < ntiles) ? j + 1 : j;
+    constexpr int NLD = TileLoader<D>::NI;
+    const auto pendK = loader.template prepare<RAGGED>(smem + (BUF ^ 1) * TILE_BYTES, Kh, jn * kBc, NK);
+    const auto pendV = loader.template prepare<RAGGED>(smem + (2 + (BUF ^ 1)) * TILE_BYTES, Vh, jn * kBc, NK);
+    auto issue_part = [&](int i) {
+      if (i < NLD) loader.template issue<RAGGED>(pendK, tid, i);
+      else if (i < 2 * NLD && VARIANT != kRowStats) loader.template issue<RAGGED>(pendV, tid, i - NLD);
+    };
+    bool issued = false;
     const int k0 = j * kBc;
     // A wave whose 32 rows all lie above this key tile has nothing to do in it (causal).
     if (!CAUSAL || (k0 <= qw + shift + 31)) {
@@ -172,7 +182,11 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
       for (int kc = 0; kc < D / 16; ++kc) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) s[kb] = mfma32(lds_row8<D>(tK, fo, 32 * kb, kc), qf[kc], s[kb]);
+        issue_part(kc);
       }
+#pragma unroll
+      for (int i = D / 16; i < 2 * NLD; ++i) issue_part(i);
+      issued = true;
       sched_reads_ahead_of_mfma<D / 8, 1, 4>();
       // ---- mask: causal (key > query) in the tile that crosses the diagonal, and keys beyond
       // the sequence end in the last, partial tile -> -inf
@@ -341,6 +355,10 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
               acc[db] = mfma32(lds_col8<D>(tV, fo, 32 * kb + 16 * cc, db), pf[kb][cc], acc[db]);
         }
       }
+    }
+    if (!issued) {      // a wave that skipped the tile still has its share of the transfer to issue
+#pragma unroll
+      for (int i = 0; i < 2 * NLD; ++i) issue_part(i);
     }
     wait_vmem();
     __syncthreads();
