@@ -57,7 +57,8 @@ template <int D, bool CAUSAL, bool RAGGED, bool GROUPED>
 __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
-    bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, int N, float alpha, Layout lay) {
+    bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, int N, float alpha, Layout lay, int pairs,
+    BlockOrder ord) {
   constexpr int TILE_BYTES = kQTile * kLdsD<D> * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   // layout: Q buffers [2][TILE_BYTES], dO buffers [2][TILE_BYTES], L2 [2][64] float, delta [2][64] float
@@ -76,13 +77,15 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
   const int NK = RAGGED ? lay.Nk : N;
   const int shift = RAGGED ? NK - N : 0;
   const int nkt = (NK + kKeysPerWG - 1) / kKeysPerWG;
-  // Under the causal mask key block kt meets nkt - kt query blocks' worth of tiles: a work-group
-  // takes block kt and then its mirror image nkt - 1 - kt, so that all work-groups carry the same
-  // load (and there are half as many to start and drain).
-  const int npw = CAUSAL ? (nkt + 1) / 2 : nkt;        // work-groups per key/value head and column part
+  // Under the causal mask key block kt meets nkt - kt query blocks' worth of tiles.  pairs != 0: a
+  // work-group takes block kt and then its mirror image nkt - 1 - kt, so that all work-groups
+  // carry the same load (and there are half as many to start and drain).  pairs == 0 (grids so
+  // small that equal but few work-groups would leave compute units idle): one block per
+  // work-group, in the order the table `ord` gives.
+  const int npw = pairs ? (nkt + 1) / 2 : nkt;         // work-groups per key/value head and column part
   constexpr int DS = kDSplit<D>;
   constexpr int NDB = D / 32 / DS;                     // 32-column blocks of dK / dV this work-group owns
-  const int wg_all = xcd_remap(blockIdx.x, gridDim.x);
+  const int wg_all = logical_wg(ord, blockIdx.x, gridDim.x);
   const int db0 = (DS > 1) ? (wg_all % DS) * NDB : 0;  // first of them
   const int wg = wg_all / DS;
   // with grouped queries a work-group serves the `group` query heads that share its key/value
@@ -114,7 +117,7 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
 
   for (int part = 0; part < (CAUSAL ? 2 : 1); ++part) {
     const int kt = (part == 0) ? kt_first : nkt - 1 - kt_first;
-    if (part == 1 && kt == kt_first) break;            // odd number of blocks: the middle one has no partner
+    if (part == 1 && (!pairs || kt == kt_first)) break;   // no partner: one block per work-group, or the middle one of an odd number
     const int k0 = kt * kKeysPerWG;
     const int kw = k0 + 32 * wave;
 
@@ -417,7 +420,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const bf16_t* __restrict__ O, bf16_t* __restrict__ dQ, float* __restrict__ delta_out, int N,
-    float alpha, Layout lay, int pairs) {
+    float alpha, Layout lay, int pairs, BlockOrder ord) {
   constexpr bool DELTA_MODE = MODE == kRecomputeDelta;
   constexpr int TILE_BYTES = kKTile * kLdsD<D> * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -435,7 +438,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
   // pairs != 0 (causal problems with enough work-groups): a work-group takes query block
   // nqt-1-idx and then its mirror image idx; together they always meet the same number of key
   // tiles, so every work-group carries the same load and the grid has no tail of heavy blocks.
-  const int wg = xcd_remap(blockIdx.x, gridDim.x);
+  const int wg = logical_wg(ord, blockIdx.x, gridDim.x);
   const int npw = pairs ? (nqt + 1) / 2 : nqt;          // work-groups per head
   const int bh = wg / npw;
   const int idx = wg % npw;
@@ -452,7 +455,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
 
   for (int part = 0; part < (pairs ? 2 : 1); ++part) {
   const int qt = pairs ? (part == 0 ? nqt - 1 - idx : idx)
-                       : nqt - 1 - (idx + (CAUSAL ? small_grid_rotation(bh, nqt, gridDim.x, D == 128 ? 768 : 1152) : 0)) % nqt;
+                       : nqt - 1 - (idx + (CAUSAL && ord.n == 0 ? small_grid_rotation(bh, nqt, gridDim.x, D == 128 ? 768 : 1152) : 0)) % nqt;
   if (part == 1 && qt == nqt - 1 - idx) break;        // odd number of blocks: the middle one has no partner
   const int q0 = qt * kQPerWG;
   const int qw = q0 + 32 * wave;
@@ -638,9 +641,17 @@ static hipError_t launch_dkdv(const void* Q, const void* K, const void* V, const
   hipError_t e;
   if ((e = set_smem(k, smem, set)) != hipSuccess) return e;
   const int nkt = ((RAGGED ? lay.Nk : N) + kKeysPerWG - 1) / kKeysPerWG;
-  hipLaunchKernelGGL(k, dim3((BH / lay.group) * (CAUSAL ? (nkt + 1) / 2 : nkt) * kDSplit<D>), dim3(256), smem, st, (const bf16_t*)Q,
+  // Under the causal mask: one block per work-group in a balanced order when that grid is small
+  // enough for the order table to apply, mirrored pairs of blocks otherwise.
+  static std::atomic<int> resident{0};
+  static thread_local OrderCache cache;
+  const BlockOrder* ord = &kNoOrder;
+  if (CAUSAL && kDSplit<D> == 1)
+    ord = &small_grid_order(cache, (BH / lay.group) * nkt, nkt, resident_per_cu(k, smem, resident));
+  const int pairs = (CAUSAL && ord->n == 0) ? 1 : 0;
+  hipLaunchKernelGGL(k, dim3((BH / lay.group) * (pairs ? (nkt + 1) / 2 : nkt) * kDSplit<D>), dim3(256), smem, st, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
-                     (bf16_t*)dK, (bf16_t*)dV, N, alpha, lay);
+                     (bf16_t*)dK, (bf16_t*)dV, N, alpha, lay, pairs, *ord);
   return hipGetLastError();
 }
 
@@ -657,9 +668,14 @@ static hipError_t launch_dq(const void* Q, const void* K, const void* V, const v
   // leaves at least two full rounds of work-groups
   const int nqt = (N + kQPerWG - 1) / kQPerWG;
   const int pairs = (CAUSAL && (long long)BH * ((nqt + 1) / 2) >= 1024) ? 1 : 0;
-  hipLaunchKernelGGL(k, dim3(BH * (pairs ? (nqt + 1) / 2 : nqt)), dim3(256), smem, st, (const bf16_t*)Q,
+  const int grid = BH * (pairs ? (nqt + 1) / 2 : nqt);
+  static std::atomic<int> resident{0};
+  static thread_local OrderCache cache;
+  const BlockOrder& ord = (CAUSAL && !pairs)
+      ? small_grid_order(cache, grid, nqt, resident_per_cu(k, smem, resident)) : kNoOrder;
+  hipLaunchKernelGGL(k, dim3(grid), dim3(256), smem, st, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
-                     (const bf16_t*)O, (bf16_t*)dQ, delta_out, N, alpha, lay, pairs);
+                     (const bf16_t*)O, (bf16_t*)dQ, delta_out, N, alpha, lay, pairs, ord);
   return hipGetLastError();
 }
 

@@ -10,8 +10,10 @@
 // tile can be fed back as a B operand: registers 8c..8c+7 of a lane are the k-slots (h, 0..7)
 // of 16-wide k-chunk c, i.e. k-slot (h, j) of chunk c  <->  tile row 16c + 8*(j/4) + 4h + (j%4).
 #pragma once
+#include "block_order.hpp"
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 
 typedef __bf16 bf16_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -376,6 +378,14 @@ DEVI int xcd_remap(int id, int n) {
   return (id & 7) * (n >> 3) + (id >> 3);
 }
 
+// Logical id of a work-group: with an order table (block_order.hpp) the s-th work-group of an XCD
+// takes item pos[s] of the XCD's contiguous share of the grid, otherwise the plain remap above.
+// The table is a kernel argument, i.e. read with scalar loads.
+DEVI int logical_wg(const BlockOrder& ord, int id, int n) {
+  if (ord.n == 0) return xcd_remap(id, n);
+  return (id & 7) * (n >> 3) + ord.pos[id >> 3];
+}
+
 // Rotation of the causal block order of one head, for grids small enough to be resident all at
 // once or nearly so (at most `capacity` work-groups, which callers set to 1.5x what the chip
 // holds of that kernel: measured, the rotation wins up to one and a half rounds of work-groups;
@@ -388,4 +398,38 @@ DEVI int small_grid_rotation(int bh, int nblk, int grid, int capacity) {
   if (grid > capacity || (grid & 7) != 0) return 0;
   const int first = (bh * nblk) % (grid >> 3);     // dispatch sequence number of the head's first block inside its XCD
   return (3 * (first >> 5)) % nblk;
+}
+
+// ---- host side of the order table --------------------------------------------------------------
+constexpr int kNumCUs = 256;
+
+// Work-groups of `kern` (256 threads, `smem` bytes of dynamic LDS) that a compute unit holds at
+// once; asked of the runtime once per kernel instantiation.
+template <class KernT>
+static int resident_per_cu(KernT kern, int smem, std::atomic<int>& cached) {
+  int r = cached.load(std::memory_order_relaxed);
+  if (r == 0) {
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&r, reinterpret_cast<const void*>(kern), 256, smem) != hipSuccess || r <= 0)
+      r = 1;
+    cached.store(r, std::memory_order_relaxed);
+  }
+  return r;
+}
+
+// The table for a causal grid of `grid` one-block work-groups with `nblk` blocks per head; empty
+// (n = 0) unless the grid is at most one and a half rounds of work-groups, a multiple of 8, and
+// every XCD's share holds whole heads.  The last table is kept (one per calling thread and kernel
+// instantiation), so a training loop computes it once.
+struct OrderCache {
+  int grid = -1, nblk = -1, resident = -1;
+  BlockOrder ord;
+};
+static const BlockOrder kNoOrder{};
+static const BlockOrder& small_grid_order(OrderCache& c, int grid, int nblk, int resident) {
+  if (c.grid != grid || c.nblk != nblk || c.resident != resident) {
+    c.grid = grid; c.nblk = nblk; c.resident = resident;
+    c.ord.n = 0;
+    if ((grid & 7) == 0 && 2LL * grid <= 3LL * kNumCUs * resident) fill_block_order(c.ord, grid >> 3, nblk, resident);
+  }
+  return c.ord;
 }

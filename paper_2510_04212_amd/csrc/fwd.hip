@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256)
 __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 128 ? 1 : 8)))) void attn_fwd_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, float* __restrict__ LSE, int N, float alpha, float beta, float eps,
-    FwdExtras ex, Layout lay, int pairs) {
+    FwdExtras ex, Layout lay, int pairs, BlockOrder ord) {
   constexpr int TILE_BYTES = kBc * kLdsD<D> * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   // layout: K buffers [2][TILE_BYTES], then V buffers [2][TILE_BYTES]
@@ -88,7 +88,7 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
   // nqt-1-idx and then its mirror image idx, which together always meet the same number of key
   // tiles, so every work-group carries the same load, there is no tail of heavy blocks at the
   // end of the grid, and half as many work-groups have to start and drain.
-  const int wg = xcd_remap(blockIdx.x, gridDim.x);
+  const int wg = logical_wg(ord, blockIdx.x, gridDim.x);
   const int npw = pairs ? (nqt + 1) / 2 : nqt;          // work-groups per head
   const int bh = wg / npw;
   const int idx = wg % npw;
@@ -110,7 +110,7 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
   for (int part = 0; part < (pairs ? 2 : 1); ++part) {
   // heavy (late) query blocks first under the causal mask
   const int qt = pairs ? (part == 0 ? nqt - 1 - idx : idx)
-                       : nqt - 1 - (idx + (CAUSAL ? small_grid_rotation(bh, nqt, gridDim.x, D == 128 ? 768 : 1536) : 0)) % nqt;
+                       : nqt - 1 - (idx + (CAUSAL && ord.n == 0 ? small_grid_rotation(bh, nqt, gridDim.x, D == 128 ? 768 : 1536) : 0)) % nqt;
   if (part == 1 && qt == nqt - 1 - idx) break;        // odd number of blocks: the middle one has no partner
   const int q0 = qt * kBr;
   const int qw = q0 + 32 * wave;                 // first query row of this wave
@@ -449,8 +449,13 @@ static hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* 
   const int nqt = (N + kBr - 1) / kBr;
   const int pairs = (CAUSAL && (long long)BH * ((nqt + 1) / 2) >= 1024) ? 1 : 0;
   dim3 grid(BH * (pairs ? (nqt + 1) / 2 : nqt));
+  // small causal grids: the block order that balances the compute units (block_order.hpp)
+  static std::atomic<int> resident{0};
+  static thread_local OrderCache cache;
+  const BlockOrder& ord = (CAUSAL && !pairs)
+      ? small_grid_order(cache, (int)grid.x, nqt, resident_per_cu(kern, smem, resident)) : kNoOrder;
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, (const bf16_t*)Q, (const bf16_t*)K,
-                     (const bf16_t*)V, (bf16_t*)O, LSE, N, alpha, beta, eps, ex, lay, pairs);
+                     (const bf16_t*)V, (bf16_t*)O, LSE, N, alpha, beta, eps, ex, lay, pairs, ord);
   return hipGetLastError();
 }
 

@@ -486,6 +486,27 @@ def test_random_shapes_against_the_oracle(lib, seed):
             check_head(got, x, b, h, causal, alpha, variant, label=label)
 
 
+@pytest.mark.parametrize("B,H,N,d", [(1, 8, 1024, 64), (8, 12, 1024, 64), (2, 8, 1536, 64), (16, 8, 512, 64),
+                                     (3, 8, 1024, 128), (2, 4, 2048, 128), (1, 16, 640, 128), (1, 8, 384, 32)])
+def test_small_causal_grids_visit_every_block_once(lib, B, H, N, d):
+    """Small causal grids take their blocks in a table-driven order that balances the compute
+    units.  With the same data in every head, a block that was skipped shows as NaN (the outputs
+    are pre-filled with it), one computed from the wrong place as a head that differs from head 0;
+    head (0, 0) is then held against the oracle."""
+    gen = torch.Generator().manual_seed(1000 + N + d + B)
+    one = coverage_inputs(1, 1, N, d, gen)
+    x = {k: v.expand(B, H, N, d).contiguous() for k, v in one.items()}
+    alpha = 1.0 / np.sqrt(d)
+    for variant in (0, 1):
+        got = run_gpu(lib, x, True, alpha, variant)
+        for name in ("O", "L", "dQ", "dK", "dV"):
+            t = got[name].float()
+            assert torch.isfinite(t).all(), name
+            first = t[0, 0]
+            assert torch.equal(t, first.expand_as(t)), name
+        check_head(got, x, 0, 0, True, alpha, variant, label=f"small grid {B}x{H}x{N}x{d} v{variant}")
+
+
 def test_step_is_capturable_in_a_graph(lib):
     """The library neither allocates nor synchronises, so a forward + backward can be captured
     into a HIP graph; several replays, with eager work between them, reproduce the eager result."""
