@@ -641,13 +641,16 @@ static hipError_t launch_dkdv(const void* Q, const void* K, const void* V, const
   hipError_t e;
   if ((e = set_smem(k, smem, set)) != hipSuccess) return e;
   const int nkt = ((RAGGED ? lay.Nk : N) + kKeysPerWG - 1) / kKeysPerWG;
-  // Under the causal mask: one block per work-group in a balanced order when that grid is small
-  // enough for the order table to apply, mirrored pairs of blocks otherwise.
+  // Under the causal mask: one block per work-group in a balanced order when that grid is at most
+  // one and a half rounds of work-groups (measured: beyond that, mirrored pairs of blocks are as
+  // fast or 2 % faster for this kernel), mirrored pairs otherwise.
   static std::atomic<int> resident{0};
   static thread_local OrderCache cache;
   const BlockOrder* ord = &kNoOrder;
-  if (CAUSAL && kDSplit<D> == 1)
-    ord = &small_grid_order(cache, (BH / lay.group) * nkt, nkt, resident_per_cu(k, smem, resident));
+  if (CAUSAL && kDSplit<D> == 1) {
+    const int res = resident_per_cu(k, smem, resident);
+    ord = &small_grid_order(cache, (BH / lay.group) * nkt, nkt, res, 3LL * kNumCUs * res / 2);
+  }
   const int pairs = (CAUSAL && ord->n == 0) ? 1 : 0;
   hipLaunchKernelGGL(k, dim3((BH / lay.group) * (pairs ? (nkt + 1) / 2 : nkt) * kDSplit<D>), dim3(256), smem, st, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
@@ -672,7 +675,7 @@ static hipError_t launch_dq(const void* Q, const void* K, const void* V, const v
   static std::atomic<int> resident{0};
   static thread_local OrderCache cache;
   const BlockOrder& ord = (CAUSAL && !pairs)
-      ? small_grid_order(cache, grid, nqt, resident_per_cu(k, smem, resident)) : kNoOrder;
+      ? small_grid_order(cache, grid, nqt, resident_per_cu(k, smem, resident), 8 * kMaxOrder) : kNoOrder;
   hipLaunchKernelGGL(k, dim3(grid), dim3(256), smem, st, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, delta,
                      (const bf16_t*)O, (bf16_t*)dQ, delta_out, N, alpha, lay, pairs, ord);

@@ -417,19 +417,19 @@ static int resident_per_cu(KernT kern, int smem, std::atomic<int>& cached) {
 }
 
 // The table for a causal grid of `grid` one-block work-groups with `nblk` blocks per head; empty
-// (n = 0) unless the grid is at most one and a half rounds of work-groups, a multiple of 8, and
-// every XCD's share holds whole heads.  The last table is kept (one per calling thread and kernel
+// (n = 0) unless the grid is at most `max_grid`, a multiple of 8, every XCD's share holds whole
+// heads and fits the table.  The last table is kept (one per calling thread and kernel
 // instantiation), so a training loop computes it once.
 struct OrderCache {
   int grid = -1, nblk = -1, resident = -1;
   BlockOrder ord;
 };
 static const BlockOrder kNoOrder{};
-static const BlockOrder& small_grid_order(OrderCache& c, int grid, int nblk, int resident) {
+static const BlockOrder& small_grid_order(OrderCache& c, int grid, int nblk, int resident, long long max_grid) {
   if (c.grid != grid || c.nblk != nblk || c.resident != resident) {
     c.grid = grid; c.nblk = nblk; c.resident = resident;
     c.ord.n = 0;
-    if ((grid & 7) == 0 && 2LL * grid <= 3LL * kNumCUs * resident) fill_block_order(c.ord, grid >> 3, nblk, resident);
+    if ((grid & 7) == 0 && grid <= max_grid) fill_block_order(c.ord, grid >> 3, nblk, resident);
   }
   return c.ord;
 }

@@ -487,10 +487,11 @@ def test_random_shapes_against_the_oracle(lib, seed):
 
 
 @pytest.mark.parametrize("B,H,N,d", [(1, 8, 1024, 64), (8, 12, 1024, 64), (2, 8, 1536, 64), (16, 8, 512, 64),
-                                     (3, 8, 1024, 128), (2, 4, 2048, 128), (1, 16, 640, 128), (1, 8, 384, 32)])
+                                     (3, 8, 1024, 128), (2, 4, 2048, 128), (1, 16, 640, 128), (1, 8, 384, 32),
+                                     (4, 32, 1024, 128), (8, 24, 1024, 64)])
 def test_small_causal_grids_visit_every_block_once(lib, B, H, N, d):
-    """Small causal grids take their blocks in a table-driven order that balances the compute
-    units.  With the same data in every head, a block that was skipped shows as NaN (the outputs
+    """Causal grids with one block per work-group (up to a few rounds of work-groups) take their
+    blocks in a table-driven order that balances the compute units.  With the same data in every head, a block that was skipped shows as NaN (the outputs
     are pre-filled with it), one computed from the wrong place as a head that differs from head 0;
     head (0, 0) is then held against the oracle."""
     gen = torch.Generator().manual_seed(1000 + N + d + B)
