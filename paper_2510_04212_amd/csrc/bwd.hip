@@ -2,7 +2,8 @@
 // gradient needs a cross-work-group reduction (no atomics, deterministic):
 //
 //   attn_bwd_dkdv_kernel  one work-group per (batch, head, 128-key block) -- under the causal mask
-//                         per pair of mirrored blocks, one after the other; K_j / V_j fragments
+//                         per pair of mirrored blocks, one after the other, unless the grid is
+//                         small (then one block each, in a balanced order); K_j / V_j fragments
 //                         stay in registers, query tiles (Q_i, dO_i, L_i, delta_i; 64 rows) stream
 //                         through LDS.  Per tile:  S = Q_i K_j^T,  P = exp(S - L),  dP = dO_i V_j^T,
 //                         dS = P o (dP - delta),  dV_j^T += dO_i^T P,  dK_j^T += Q_i^T dS.
@@ -438,6 +439,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
   // pairs != 0 (causal problems with enough work-groups): a work-group takes query block
   // nqt-1-idx and then its mirror image idx; together they always meet the same number of key
   // tiles, so every work-group carries the same load and the grid has no tail of heavy blocks.
+  // pairs == 0: one block per work-group, for causal grids in the order the table `ord` gives.
   const int wg = logical_wg(ord, blockIdx.x, gridDim.x);
   const int npw = pairs ? (nqt + 1) / 2 : nqt;          // work-groups per head
   const int bh = wg / npw;

@@ -87,7 +87,9 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
   // pairs != 0 (causal problems with enough work-groups): a work-group takes query block
   // nqt-1-idx and then its mirror image idx, which together always meet the same number of key
   // tiles, so every work-group carries the same load, there is no tail of heavy blocks at the
-  // end of the grid, and half as many work-groups have to start and drain.
+  // end of the grid, and half as many work-groups have to start and drain.  pairs == 0: one
+  // block per work-group, for causal grids in the order the table `ord` gives (or, where the
+  // table does not apply, heavy blocks first with a per-lap rotation on small grids).
   const int wg = logical_wg(ord, blockIdx.x, gridDim.x);
   const int npw = pairs ? (nqt + 1) / 2 : nqt;          // work-groups per head
   const int bh = wg / npw;
@@ -445,7 +447,7 @@ static hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* 
   }
   // Under the causal mask a work-group takes a query block and its mirror image (equal work for
   // all) when that still leaves at least two full rounds of work-groups (two fit a CU, 256 CUs);
-  // smaller grids keep one block per work-group.
+  // smaller grids keep one block per work-group, in a balanced order (below).
   const int nqt = (N + kBr - 1) / kBr;
   const int pairs = (CAUSAL && (long long)BH * ((nqt + 1) / 2) >= 1024) ? 1 : 0;
   dim3 grid(BH * (pairs ? (nqt + 1) / 2 : nqt));
