@@ -53,6 +53,9 @@ DEVI void store_acc_T(bf16_t* dst_row, const f32x16 (&acc)[NDB], float scale, in
 // work-groups per key block, each recomputing S and dP), and the four-phase pipeline, whose
 // phases assume as many update as score instructions, is not used.
 template <int D> constexpr int kDSplit = D > 128 ? 2 : 1;
+// dK / dV rows leave through a per-wave LDS staging area (store_rows_staged) where the row width
+// allows it and LDS has room for it next to the tiles (not at D = 256).
+template <int D> constexpr bool kStagedDkDv = kCanStage<D / 32 / kDSplit<D>> && D <= 128;
 
 template <int D, bool CAUSAL, bool RAGGED, bool GROUPED>
 __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
@@ -67,6 +70,7 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
   char* ldsdO = smem + 2 * TILE_BYTES;
   float* ldsL = reinterpret_cast<float*>(smem + 4 * TILE_BYTES);
   float* ldsD = ldsL + 2 * kQTile;
+  // behind them: one staging area per wave for the output rows (store_rows_staged)
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -396,7 +400,20 @@ __global__ __launch_bounds__(256, D <= 64 ? 2 : 1) void attn_bwd_dkdv_kernel(
         }
       }
     }
-    if (!RAGGED || kw + r < NK) {
+    if constexpr (kStagedDkDv<D>) {
+      char* stage = smem + 4 * TILE_BYTES + 4 * kQTile * (int)sizeof(float);
+      const int rows_valid = RAGGED ? NK - kw : 32;
+      auto rounded = [&](const f32x16 (&acc)[NDB], float scale) {
+        return [&acc, scale](int db, int g) {
+          bf16x4 o4;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o4[e] = (bf16_t)(acc[db][4 * g + e] * scale);
+          return o4;
+        };
+      };
+      store_rows_staged<NDB>(stage, rounded(dVt, 1.0f), dV + 32 * db0 + head_off + (size_t)kw * sn, sn, rows_valid, tid);
+      store_rows_staged<NDB>(stage, rounded(dKt, alpha), dK + 32 * db0 + head_off + (size_t)kw * sn, sn, rows_valid, tid);
+    } else if (!RAGGED || kw + r < NK) {
       store_acc_T<NDB>(dV + 32 * db0 + head_off + (size_t)(kw + r) * sn, dVt, 1.0f, h);
       store_acc_T<NDB>(dK + 32 * db0 + head_off + (size_t)(kw + r) * sn, dKt, alpha, h);
     }
@@ -456,6 +473,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
   frag_offsets_add_base<D>(fo, lds_address(smem));
 
   for (int part = 0; part < (pairs ? 2 : 1); ++part) {
+  if (part > 0) __syncthreads();                      // the first block's output staging is done with the tile buffers
   const int qt = pairs ? (part == 0 ? nqt - 1 - idx : idx)
                        : nqt - 1 - (idx + (CAUSAL && ord.n == 0 ? small_grid_rotation(bh, nqt, gridDim.x, D == 128 ? 768 : 1152) : 0)) % nqt;
   if (part == 1 && qt == nqt - 1 - idx) break;        // odd number of blocks: the middle one has no partner
@@ -620,7 +638,20 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_bwd_dq_kernel(
     if (h == 0 && (!RAGGED || qw + r < N)) delta_out[(size_t)bh * N + qw + r] = dsum;
     continue;
   }
-  if (!RAGGED || qw + r < N) store_acc_T<D / 32>(dQ + head_off + (size_t)(qw + r) * sn, dQt, alpha, h);
+  if constexpr (kCanStage<D / 32>) {
+    // the tile buffers are free now (every wave is past the last tile's barrier): they serve as
+    // the staging areas of store_rows_staged; the barrier at the top of the part loop keeps the
+    // next block's tile transfers from overwriting an area a slower wave is still reading
+    auto piece = [&](int db, int g) {
+      bf16x4 o4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o4[e] = (bf16_t)(dQt[db][4 * g + e] * alpha);
+      return o4;
+    };
+    store_rows_staged<D / 32>(smem, piece, dQ + head_off + (size_t)qw * sn, sn, RAGGED ? N - qw : 32, tid);
+  } else if (!RAGGED || qw + r < N) {
+    store_acc_T<D / 32>(dQ + head_off + (size_t)(qw + r) * sn, dQt, alpha, h);
+  }
   }   // part
 }
 
@@ -637,7 +668,9 @@ template <int D, bool CAUSAL, bool RAGGED, bool GROUPED>
 static hipError_t launch_dkdv(const void* Q, const void* K, const void* V, const void* dO,
                               const float* LSE, const float* delta, void* dK, void* dV, int BH,
                               int N, float alpha, Layout lay, hipStream_t st) {
-  constexpr int smem = 4 * kQTile * kLdsD<D> * 2 + 4 * kQTile * (int)sizeof(float);
+  constexpr int NDB = D / 32 / kDSplit<D>;
+  constexpr int smem = 4 * kQTile * kLdsD<D> * 2 + 4 * kQTile * (int)sizeof(float) +
+                       (kStagedDkDv<D> ? 4 * 32 * kStagePitch<NDB> : 0);
   static std::atomic<bool> set{false};
   auto k = attn_bwd_dkdv_kernel<D, CAUSAL, RAGGED, GROUPED>;
   hipError_t e;

@@ -352,6 +352,44 @@ DEVI float divide(float x, Divisor d) {
   return __builtin_fmaf(__builtin_fmaf(-q, d.l, xs), d.r, q);
 }
 
+// Output rows of a wave that holds a 32-row tile transposed in accumulator layout (lane (r,h) has,
+// for its row r, the columns 32db + 8g + 4h .. +3 of every (db, g)): written straight from the
+// registers, every store instruction would put 8-byte pieces into 32 different rows.  Instead the
+// wave passes the tile through an LDS staging area of its own (32 rows of kStagePitch<NDB> bytes,
+// wave w's area following wave w-1's from stage_wave0 on)
+// and stores whole rows, 16 bytes per lane with consecutive lanes on consecutive chunks.  No
+// barrier is involved: the area belongs to this wave alone, and the LDS executes one wave's
+// accesses in order.  piece(db, g) returns the four bf16 values of that position; rows at or
+// beyond rows_valid are not stored.  Needs 64 % (4 NDB) == 0.
+template <int NDB> constexpr int kStagePitch = 64 * NDB + 16;   // +16: rows start 4 banks apart
+template <int NDB> constexpr bool kCanStage = (64 % (4 * NDB)) == 0;
+template <int NDB, class PieceF>
+DEVI void store_rows_staged(char* stage_wave0, PieceF&& piece, bf16_t* dst_row0, int sn, int rows_valid, int tid) {
+  static_assert(kCanStage<NDB>, "row width");
+  constexpr int PITCH = kStagePitch<NDB>;
+  constexpr int CPR = 4 * NDB;                  // 16-byte chunks per row
+  constexpr int RPI = 64 / CPR;                 // rows per store instruction
+  // The thread index goes through a copy the compiler cannot see through: every address below
+  // depends on it, and computed from the kernel's own copy they would all be formed before the
+  // tile loop and held in registers through it.
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
+  char* stage = stage_wave0 + (tid >> 6) * (32 * PITCH);
+  const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      *reinterpret_cast<bf16x4*>(stage + r * PITCH + (32 * db + 8 * g + 4 * h) * 2) = piece(db, g);
+  typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+#pragma unroll
+  for (int it = 0; it < 32 / RPI; ++it) {
+    const int row = it * RPI + lane / CPR, c = lane % CPR;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * PITCH + c * 16);
+    if (row < rows_valid) *reinterpret_cast<u32x4*>(dst_row0 + (size_t)row * sn + c * 8) = v;
+  }
+}
+
 // Issue-order hints for one scheduling region (basic block) that holds N matrix instructions,
 // each fed by PER LDS fragment reads: the reads are issued AHEAD matrix instructions before
 // their use, so that LDS latency is covered by matrix-core work instead of stalling the wave.

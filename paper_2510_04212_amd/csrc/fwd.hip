@@ -110,6 +110,7 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
   const float inv_alpha = 1.0f / alpha;
 
   for (int part = 0; part < (pairs ? 2 : 1); ++part) {
+  if (part > 0) __syncthreads();                      // the first block's output staging is done with the tile buffers
   // heavy (late) query blocks first under the causal mask
   const int qt = pairs ? (part == 0 ? nqt - 1 - idx : idx)
                        : nqt - 1 - (idx + (CAUSAL && ord.n == 0 ? small_grid_rotation(bh, nqt, gridDim.x, D == 128 ? 768 : 1536) : 0)) % nqt;
@@ -395,30 +396,44 @@ __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1, kLdsD<D> == 128 ? 2 : (D > 
     auto sw = __builtin_amdgcn_permlane32_swap((unsigned)ones_cnt, (unsigned)ones_cnt, false, false);
     ones_row = (int)(sw[0] + sw[1]);
   }
-  if (!RAGGED || q < N) {                                  // rows past the sequence end exist only as padding
-  bf16_t* Oq = O + head_off + (size_t)q * sn;
   const bool keep_obar_f32 = EXTRAS && ex.single_rounding != 0;
   const bool unseen_row = RAGGED && m == -INFINITY;        // no visible key (more queries than keys): O = 0, LSE = -inf
   const Divisor by_l = make_divisor(l);
+  auto o_piece = [&](int db, int g) {
+    bf16x4 o4;
 #pragma unroll
-  for (int db = 0; db < D / 32; ++db)
+    for (int e = 0; e < 4; ++e) {
+      const float a = acc[db][4 * g + e];
+      const float obar = keep_obar_f32 ? a : (float)(bf16_t)a;
+      o4[e] = (bf16_t)(unseen_row ? 0.f : divide(obar, by_l));
+    }
+    return o4;
+  };
+  if constexpr (kCanStage<D / 32>) {
+    // the tile buffers are free now (every wave is past the last tile's barrier) and serve as the
+    // staging areas of store_rows_staged; the barrier at the top of the part loop keeps the next
+    // block's tile transfers from overwriting an area a slower wave is still reading
+    store_rows_staged<D / 32>(smem, o_piece, O + head_off + (size_t)qw * sn, sn, RAGGED ? N - qw : 32, tid);
+  }
+  if (!RAGGED || q < N) {                                  // rows past the sequence end exist only as padding
+  if constexpr (!kCanStage<D / 32>) {
+    bf16_t* Oq = O + head_off + (size_t)q * sn;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      bf16x4 o4;
+    for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float a = acc[db][4 * g + e];
-        const float obar = keep_obar_f32 ? a : (float)(bf16_t)a;
-        o4[e] = (bf16_t)(unseen_row ? 0.f : divide(obar, by_l));
-      }
-      *reinterpret_cast<bf16x4*>(Oq + 32 * db + 8 * g + 4 * h) = o4;
-      if (EXTRAS && ex.O_hp != nullptr) {
+      for (int g = 0; g < 4; ++g) *reinterpret_cast<bf16x4*>(Oq + 32 * db + 8 * g + 4 * h) = o_piece(db, g);
+  }
+  if (EXTRAS && ex.O_hp != nullptr) {
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
         f32x4 hp;
 #pragma unroll
         for (int e = 0; e < 4; ++e) hp[e] = unseen_row ? 0.f : divide(acc[db][4 * g + e], by_l);
         *reinterpret_cast<f32x4*>(ex.O_hp + ((size_t)bh * N + q) * D + 32 * db + 8 * g + 4 * h) = hp;
       }
-    }
+  }
   if (h == 0) {
     LSE[(size_t)bh * N + q] = m + __logf(l);
     if (EXTRAS && ex.ones != nullptr) ex.ones[(size_t)bh * N + q] = ones_row;
