@@ -34,10 +34,10 @@ PEAK_HBM_GBS = 8000.0
 # scaled by the same counter's reading for a 1 GiB device copy (see profiles/mid_hbm_traffic.txt).
 # Keyed by (workload, kernel); None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("mid", "fwd"): 672143413,
-    ("mid", "delta"): 270665585,
-    ("mid", "bwd_dkdv"): 830326875,
-    ("mid", "bwd_dq"): 947291421,
+    ("mid", "fwd"): 676315946,
+    ("mid", "delta"): 270662893,
+    ("mid", "bwd_dkdv"): 816209224,
+    ("mid", "bwd_dq"): 951223775,
 }
 
 
