@@ -15,8 +15,6 @@
 // Plain C++ (no HIP): the struct is a kernel argument, the fill routine runs on the host.
 #pragma once
 #include <algorithm>
-#include <numeric>
-#include <vector>
 
 constexpr int kCUsPerXCD = 32;
 constexpr int kMaxOrder = 255;
@@ -34,9 +32,11 @@ inline bool fill_block_order(BlockOrder& ord, int per, int nblk, int resident) {
   ord.n = 0;
   if (per <= 0 || per > kMaxOrder || nblk <= 0 || per % nblk != 0 || resident <= 0) return false;
   auto weight = [&](int j) { return 2 * (nblk - j % nblk) + 1; };
-  std::vector<int> items(per);
-  std::iota(items.begin(), items.end(), 0);
-  std::stable_sort(items.begin(), items.end(), [&](int a, int b) { return weight(a) > weight(b); });
+  // the items by falling weight (heads in their own order within a weight class); no heap use,
+  // the routine runs inside kernel launches
+  unsigned short items[kMaxOrder];
+  for (int idx = 0, n = 0; idx < nblk; ++idx)
+    for (int first = 0; first < per; first += nblk) items[n++] = (unsigned short)(first + idx);
   const int slots = std::min(per, kCUsPerXCD * resident);       // positions that are placed at launch
   int cap[kCUsPerXCD], cnt[kCUsPerXCD], load[kCUsPerXCD];
   for (int c = 0; c < kCUsPerXCD; ++c) {
