@@ -356,9 +356,8 @@ DEVI float divide(float x, Divisor d) {
 // for its row r, the columns 32db + 8g + 4h .. +3 of every (db, g)): written straight from the
 // registers, every store instruction would put 8-byte pieces into 32 different rows.  Instead the
 // wave passes the tile through an LDS staging area of its own (32 rows of kStagePitch<NDB> bytes,
-// wave w's area following wave w-1's from stage_wave0 on)
-// and stores whole rows, 16 bytes per lane with consecutive lanes on consecutive chunks.  No
-// barrier is involved: the area belongs to this wave alone, and the LDS executes one wave's
+// wave w's area following wave w-1's from stage_wave0 on) and stores whole rows, 16 bytes per
+// lane with consecutive lanes on consecutive chunks.  No barrier is involved: the area belongs to this wave alone, and the LDS executes one wave's
 // accesses in order.  piece(db, g) returns the four bf16 values of that position; rows at or
 // beyond rows_valid are not stored.  Needs 64 % (4 NDB) == 0.
 template <int NDB> constexpr int kStagePitch = 64 * NDB + 16;   // +16: rows start 4 banks apart
@@ -447,8 +446,10 @@ template <class KernT>
 static int resident_per_cu(KernT kern, int smem, std::atomic<int>& cached) {
   int r = cached.load(std::memory_order_relaxed);
   if (r == 0) {
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&r, reinterpret_cast<const void*>(kern), 256, smem) != hipSuccess || r <= 0)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&r, reinterpret_cast<const void*>(kern), 256, smem) != hipSuccess || r <= 0) {
+      (void)hipGetLastError();   // the answer only steers the block order: not an error of the launch that follows
       r = 1;
+    }
     cached.store(r, std::memory_order_relaxed);
   }
   return r;
