@@ -416,6 +416,41 @@ def test_side_stream(lib):
         assert torch.equal(got[name], ref[name])
 
 
+def test_two_host_threads_on_their_own_streams(lib):
+    """The library keeps per-thread and per-kernel host state (attribute flags, the block-order
+    table of the last grid): two host threads that launch different shapes at the same time, each
+    on its own stream, get the bits a single thread gets."""
+    import threading
+    shapes = [(8, 12, 1024, 64), (2, 8, 1536, 128)]          # both take the table-driven block order
+    gens = [torch.Generator().manual_seed(77 + i) for i in range(2)]
+    xs = [coverage_inputs(*shape, gens[i]) for i, shape in enumerate(shapes)]
+    refs = [run_gpu(lib, x, True, 1.0 / np.sqrt(shape[3]), 1) for x, shape in zip(xs, shapes)]
+    streams = [torch.cuda.Stream() for _ in shapes]
+    for st in streams:
+        st.wait_stream(torch.cuda.current_stream())
+    results = [None, None]
+    errors = []
+
+    def worker(i):
+        try:
+            with torch.cuda.stream(streams[i]):
+                for _ in range(6):
+                    results[i] = run_gpu(lib, xs[i], True, 1.0 / np.sqrt(shapes[i][3]), 1, stream=streams[i])
+        except Exception as e:                                   # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for got, ref in zip(results, refs):
+        for name in ref:
+            assert torch.equal(got[name], ref[name]), name
+
+
 def test_closed_forms_on_gpu(lib):
     B, H, N, d = 1, 2, 256, 64
     g = torch.Generator().manual_seed(5)
